@@ -1,0 +1,266 @@
+/*
+ * scmoe.h — C ABI of the MI355X (gfx950) ScMoE forward-pass library.
+ *
+ * One shortcut-connected MoE block (ScMoE paper, Sec. 3.1, Eq. (7)):
+ *
+ *     y = SE(x_cur) + sum_i G(x_prev)_i * E_i(x_prev)        (+ x_cur if a residual is passed)
+ *
+ * split into the operators of the expert-parallel workflow (Sec. 2.2): gate routing,
+ * input encode (= dispatch permutation), expert computation, output decode (= combine).
+ * On one GPU the two All-to-All steps of that workflow are the identity.
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".  All buffers are
+ *    owned by the caller; the library allocates and frees no device memory and keeps no
+ *    pointer after it returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Argument checks
+ *    run synchronously on the host; kernels are enqueued on the stream and the call returns
+ *    without synchronising.
+ *  - The return value is a status code (SCMOE_OK == 0).  On an error nothing is launched.
+ *    No exception and no abort crosses the boundary.
+ *  - Matrices are row-major.  `ld*` arguments are row strides in ELEMENTS.
+ *  - `dtype` (SCMOE_F32 or SCMOE_BF16) is the storage type of activations and of the FFN
+ *    weight matrices.  Gate weights W_g, gate bias, FFN biases, gate_w and probs are
+ *    always fp32; indices, counts and offsets are int32.
+ *  - bf16 buffers must be 16-byte aligned with row strides that are multiples of 8
+ *    elements; fp32 buffers 16-byte aligned with strides that are multiples of 4.
+ *    d and F must be multiples of 8.  Violations give SCMOE_ERR_SHAPE.
+ *  - T == 0 is legal everywhere (no-op, SCMOE_OK).
+ */
+#ifndef SCMOE_H
+#define SCMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SCMOE_OK = 0,
+  SCMOE_ERR_NULL = 1,      /* a required pointer is NULL                         */
+  SCMOE_ERR_SHAPE = 2,     /* a size, stride or alignment is outside the contract */
+  SCMOE_ERR_DTYPE = 3,     /* dtype is neither SCMOE_F32 nor SCMOE_BF16           */
+  SCMOE_ERR_WORKSPACE = 4, /* the workspace passed is too small                   */
+  SCMOE_ERR_HIP = 5,       /* a HIP call failed; see scmoe_last_hip_error()       */
+  SCMOE_ERR_ARG = 6        /* an option value (mode flag, k, ...) is not supported */
+};
+
+enum { SCMOE_F32 = 0, SCMOE_BF16 = 1 };
+
+/* GELU flavour of the expert MLPs.  The paper only says the experts are MLPs (Sec. 2.1);
+ * the exact erf form 0.5 v (1 + erf(v / sqrt 2)) is the default reading. */
+enum { SCMOE_GELU_ERF = 0, SCMOE_GELU_TANH = 1 };
+
+/* How the shared expert's output and the routed output are merged (Sec. 5.2):
+ * direct add (Eq. (6)), CG-1 (Eq. (14)-(15)), CG-2 (Eq. (16)-(17)). */
+enum { SCMOE_CG_NONE = 0, SCMOE_CG_1 = 1, SCMOE_CG_2 = 2 };
+
+/* Upper limit on the number of experts accepted by the gate and dispatch kernels. */
+#define SCMOE_MAX_EXPERTS 64
+
+/* Shape and options of one layer.  Plain data, host memory, read during the call only. */
+typedef struct scmoe_desc {
+  int32_t T;         /* tokens                                                        */
+  int32_t d;         /* model width                                                   */
+  int32_t F;         /* FFN hidden width                                              */
+  int32_t E;         /* routed experts, 1..SCMOE_MAX_EXPERTS                          */
+  int32_t k;         /* experts per token: 1 for scmoe_layer_forward, 1 or 2 for the
+                        standard layer                                                */
+  int32_t capacity;  /* C: rows an expert accepts; >= T*k means unbounded             */
+  int32_t dtype;     /* SCMOE_F32 / SCMOE_BF16                                        */
+  int32_t gelu_mode; /* SCMOE_GELU_ERF / SCMOE_GELU_TANH                              */
+  int32_t normalize; /* gate weights: 0 = softmax over all E logits evaluated at the
+                        selected experts; 1 = softmax over the k selected logits only
+                        (Eq. (2) taken literally; for k = 1 that weight is 1)          */
+  int32_t cg_mode;   /* SCMOE_CG_NONE / SCMOE_CG_1 / SCMOE_CG_2                        */
+} scmoe_desc;
+
+/* Weights of one layer.  Host struct of device pointers. */
+typedef struct scmoe_weights {
+  const float* W_g;  /* [d, E] gate matrix of Eq. (4), fp32                            */
+  const float* bias; /* [E] deterministic additive gate term in the slot of Eq. (4)'s
+                        epsilon, or NULL                                               */
+  const void* W1;    /* [E, F, d] first linear layer of every routed expert ([out,in]) */
+  const float* b1;   /* [E, F] or NULL                                                 */
+  const void* W2;    /* [E, d, F] second linear layer ([out,in])                       */
+  const float* b2;   /* [E, d] or NULL                                                 */
+  const void* W1s;   /* [F, d] shared expert (unused by moe_topk_layer_forward)        */
+  const float* b1s;  /* [F] or NULL                                                    */
+  const void* W2s;   /* [d, F]                                                         */
+  const float* b2s;  /* [d] or NULL                                                    */
+  const float* W_cg; /* [1, d] (CG-1) or [2, d] (CG-2), fp32; NULL when cg_mode == 0   */
+} scmoe_weights;
+
+/* Optional copies of the routing state of a layer call.  Each member may be NULL. */
+typedef struct scmoe_routing_out {
+  int32_t* expert_idx; /* [T*k]                                                       */
+  float* gate_w;       /* [T*k]                                                       */
+  int32_t* counts;     /* [E]                                                         */
+  int32_t* offsets;    /* [E+1]                                                       */
+  int32_t* dst_row;    /* [T*k]                                                       */
+  int32_t* src_token;  /* [min(T*k, E*C)]                                             */
+} scmoe_routing_out;
+
+/* Text for a status code.  Host, static storage. */
+const char* scmoe_status_string(int status);
+
+/* hipError_t (as int) of the most recent SCMOE_ERR_HIP on the calling thread. */
+int scmoe_last_hip_error(void);
+
+/* Capacity from a capacity factor (Tables 8-9 give only the factor): C = ceil(cf*k*T/E),
+ * the ceiling taken after removing rounding noise of the double product.  Host only.
+ * `C` is a host pointer. */
+int scmoe_capacity(int32_t T, int32_t E, int32_t k, double cf, int32_t* C);
+
+/*
+ * Gate routing, top-1 (Eq. (2)-(4) with k = 1 and epsilon = 0; ScMoE applies it to the
+ * preceding-layer representation, Sec. 3.1).
+ *
+ *   logit[t,e] = fp32 chain  acc = 0; for i = 0..d-1: acc = fma(x[t,i], W_g[i,e], acc);
+ *                then  + bias[e]  (one rounded add; skipped when bias == NULL)
+ *   expert_idx[t] = argmax_e logit[t,e], lowest e on ties, a NaN never wins
+ *   gate_w[t]     = softmax(logit[t,:])[expert_idx[t]]   (normalize == 0)
+ *                 = 1                                    (normalize == 1)
+ *   probs[t,:]    = softmax(logit[t,:])                  (optional, may be NULL)
+ *
+ * The ascending-i single-FMA chain is part of the contract: it fixes the logits bit for
+ * bit and with them the routing.  x: [T, d] with stride ldx, dtype as given (bf16 is
+ * widened exactly).  W_g: [d, E] fp32, E <= SCMOE_MAX_EXPERTS.
+ */
+int scmoe_gate_top1(const void* x, int64_t ldx, int32_t dtype, const float* W_g,
+                    const float* bias, int32_t T, int32_t d, int32_t E, int32_t normalize,
+                    int32_t* expert_idx, float* gate_w, float* probs, void* stream);
+
+/*
+ * Gate routing, top-2 (Eq. (2)-(4) with k = 2), used by the standard MoE layer that the
+ * paper takes as its baseline.  Same logits as above.  expert_idx[t,0] is the arg max,
+ * expert_idx[t,1] the arg max among the remaining experts (lowest index on ties; needs
+ * E >= 2).  normalize == 1: gate_w[t,:] = softmax over the two selected logits (Eq. (2));
+ * normalize == 0: the two entries of the full softmax.
+ * expert_idx, gate_w: [T, 2] row-major.
+ */
+int scmoe_gate_top2(const void* x, int64_t ldx, int32_t dtype, const float* W_g,
+                    const float* bias, int32_t T, int32_t d, int32_t E, int32_t normalize,
+                    int32_t* expert_idx, float* gate_w, float* probs, void* stream);
+
+/* Bytes of workspace scmoe_dispatch needs.  `out` is a host pointer. */
+int scmoe_dispatch_workspace_bytes(int32_t T, int32_t E, int32_t k, size_t* out);
+
+/*
+ * Input encode (Sec. 2.2): the capacity-bounded permutation of token rows into contiguous
+ * per-expert segments.
+ *
+ * Items are the (token t, choice j) pairs, ordered by (j, t): every first choice comes
+ * before any second choice.  The slot of an item inside its expert e is the number of
+ * earlier items routed to e; the item is kept iff slot < capacity.
+ *
+ *   counts[e]        = min(#items routed to e, capacity)
+ *   offsets[0..E]    = exclusive prefix sum of counts; offsets[E] = K, the kept items
+ *   dst_row[t*k + j] = offsets[e] + slot if kept, else -1
+ *   src_token[r]     = t for the item stored in packed row r, r < K (entries >= K are
+ *                      left untouched)
+ *   x_perm[r, :]     = x[src_token[r], :]   (raw row copy; may be NULL to skip the copy)
+ *
+ * expert_idx: [T*k], values in [0, E) — values outside that range are treated as
+ * dropped.  src_token and x_perm must have room for min(T*k, E*capacity) rows.
+ * The result is deterministic (a stable counting sort), not dependent on scheduling.
+ */
+int scmoe_dispatch(const void* x, int64_t ldx, int32_t dtype, const int32_t* expert_idx,
+                   int32_t T, int32_t d, int32_t E, int32_t k, int32_t capacity,
+                   int32_t* counts, int32_t* offsets, int32_t* dst_row, int32_t* src_token,
+                   void* x_perm, int64_t ld_perm, void* workspace, size_t ws_bytes,
+                   void* stream);
+
+/*
+ * Expert computation (Eq. (1); the experts are two-layer MLPs, Sec. 2.1) as a grouped
+ * GEMM over packed segments:
+ *
+ *   for e in 0..E-1, r in [offsets[e], offsets[e+1]):
+ *       hidden[r, :] = GELU(W1[e] . x_perm[r, :] + b1[e])
+ *       y_perm[r, :] = W2[e] . hidden[r, :] + b2[e]
+ *
+ * offsets: [E+1] on the DEVICE (read by the kernels, never by the host); offsets[E] must
+ * not exceed max_rows, the number of rows x_perm / hidden / y_perm hold (rows past
+ * offsets[E] are not touched).  W1: [E, F, d], W2: [E, d, F] in `dtype`; b1 [E, F],
+ * b2 [E, d] fp32 or NULL.  hidden: caller scratch [max_rows, F] in `dtype`, row stride F.
+ * bf16: fp32 accumulation, hidden and y_perm rounded to bf16 (RNE) on store.
+ * With E = 1 and offsets = {0, T} this is the dense MLP used for the shared expert
+ * (Eq. (6)).
+ */
+int scmoe_expert_ffn(const void* x_perm, int64_t ld_perm, int32_t dtype,
+                     const int32_t* offsets, int32_t max_rows, int32_t E, int32_t d,
+                     int32_t F, const void* W1, const float* b1, const void* W2,
+                     const float* b2, void* hidden, void* y_perm, int64_t ldy,
+                     int32_t gelu_mode, void* stream);
+
+/*
+ * Output decode (Sec. 2.2) fused with the merge of Eq. (6)/(7):
+ *
+ *   y[t,:] = c0[t] * base[t,:] + c1[t] * sum_j gate_w[t*k+j] * y_perm[dst_row[t*k+j], :]
+ *            + residual[t,:]
+ *
+ * Terms with dst_row == -1 are skipped (a dropped token's expert output is exactly 0).
+ * base (the shared expert's output) and residual may each be NULL.  c0 = c1 = 1 unless a
+ * coefficient gate is given: coef != NULL holds [T, 2] fp32 pairs (c0, c1) as produced by
+ * scmoe_coef_gate.  Arithmetic in fp32; y is rounded once on store.  y may alias base or
+ * residual when the strides match.
+ */
+int scmoe_combine(const void* y_perm, int64_t ldyp, int32_t dtype, const int32_t* dst_row,
+                  const float* gate_w, int32_t T, int32_t d, int32_t k, const void* base,
+                  int64_t ldbase, const void* residual, int64_t ldres, const float* coef,
+                  void* y, int64_t ldy, void* stream);
+
+/*
+ * Coefficient gate (Sec. 5.2).  CG-1, Eq. (14): c0 = sigmoid(W_cg . x), c1 = 1.
+ * CG-2, Eq. (16): (c0, c1) = softmax(W_cg . x) with W_cg of two rows.  The dot products
+ * are fp32 sums (no bit-exact contract; they feed no integer decision).
+ * x: [T, d]; W_cg: [1, d] or [2, d] fp32; coef: [T, 2] fp32.
+ */
+int scmoe_coef_gate(const void* x, int64_t ldx, int32_t dtype, const float* W_cg,
+                    int32_t cg_mode, int32_t T, int32_t d, float* coef, void* stream);
+
+/* Bytes of workspace a layer call needs for `desc`.  `desc`, `out`: host pointers. */
+int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out);
+
+/*
+ * One ScMoE block forward (Eq. (7); module form: without the residual unless given):
+ *
+ *   y = SE(x_cur) + sum_i G(x_prev)_i E_i(x_prev)
+ *
+ * = gate_top1(x_prev) -> dispatch -> expert_ffn -> combine(base = SE(x_cur)).
+ * The shared expert depends on x_cur only and the routed chain on x_prev only (Sec. 3.2):
+ * with stream_aux != NULL the shared expert's GEMMs are enqueued on stream_aux and the
+ * routed chain on stream_main, forked and joined with events; with stream_aux == NULL
+ * everything runs in order on stream_main.  The result is ready on stream_main.
+ * desc->k must be 1.  With desc->cg_mode != 0 the coefficient gate reads x_cur.
+ * residual may be NULL.  routing may be NULL.  No host synchronisation happens inside.
+ */
+int scmoe_layer_forward(const scmoe_desc* desc, const void* x_prev, int64_t ld_prev,
+                        const void* x_cur, int64_t ld_cur, const scmoe_weights* w,
+                        const void* residual, int64_t ldres, void* y, int64_t ldy,
+                        const scmoe_routing_out* routing, void* workspace, size_t ws_bytes,
+                        void* stream_main, void* stream_aux);
+
+/*
+ * Standard top-k MoE layer on the current-layer representation (Eq. (1)-(4); k = 2 is the
+ * baseline the paper compares with, Fig. 2(a)):  y = sum_j gate_w[t,j] E_{idx[t,j]}(x[t]).
+ * desc->k in {1, 2}.  Shared-expert members of `w` are ignored.
+ */
+int moe_topk_layer_forward(const scmoe_desc* desc, const void* x, int64_t ldx,
+                           const scmoe_weights* w, void* y, int64_t ldy,
+                           const scmoe_routing_out* routing, void* workspace,
+                           size_t ws_bytes, void* stream);
+
+/* The k = 2 case of moe_topk_layer_forward under the name the baseline is known by. */
+int moe_top2_layer_forward(const scmoe_desc* desc, const void* x, int64_t ldx,
+                           const scmoe_weights* w, void* y, int64_t ldy,
+                           const scmoe_routing_out* routing, void* workspace,
+                           size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCMOE_H */
