@@ -1,0 +1,82 @@
+// Internal helpers shared by the HIP sources of libscmoe (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "scmoe.h"
+
+namespace scmoe {
+
+// Last HIP error seen by an entry point on this thread (reported by scmoe_last_hip_error).
+extern thread_local int g_last_hip_error;
+
+inline int hip_fail(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  return SCMOE_ERR_HIP;
+}
+
+// Status of the kernel launch that was just enqueued.
+inline int launch_status() {
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? SCMOE_OK : hip_fail(e);
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int elem_bytes(int dtype) { return dtype == SCMOE_BF16 ? 2 : 4; }
+
+// Elements per 16-byte vector.
+inline int vec_elems(int dtype) { return dtype == SCMOE_BF16 ? 8 : 4; }
+
+inline bool dtype_ok(int dtype) { return dtype == SCMOE_F32 || dtype == SCMOE_BF16; }
+
+// A matrix view is acceptable when its base is 16-byte aligned and its row stride keeps
+// every row 16-byte aligned and covers `cols`.
+inline bool view_ok(const void* p, int64_t ld, int64_t cols, int dtype) {
+  return aligned16(p) && ld >= cols && (ld % vec_elems(dtype)) == 0;
+}
+
+// ---- bf16 <-> fp32 on the device (bit manipulation; round to nearest even) -------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t v) {
+  return __uint_as_float(static_cast<uint32_t>(v) << 16);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7f800000u) == 0x7f800000u) {  // inf / nan: keep the class, quiet a nan
+    return static_cast<uint16_t>((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
+  }
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+
+// GELU of the expert MLPs: exact erf form or the tanh approximation.
+__device__ __forceinline__ float gelu_f32(float v, int mode) {
+  if (mode == SCMOE_GELU_TANH) {
+    const float c = 0.7978845608028654f;
+    return 0.5f * v * (1.0f + tanhf(c * (v + 0.044715f * v * v * v)));
+  }
+  return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
+}
+
+// ---- entry points implemented in one source and used by the layer orchestration --------
+int ffn_generic(const void* x, int64_t ldx, int dtype, const int32_t* offsets, int max_rows,
+                int E, int d, int F, const void* W1, const float* b1, const void* W2,
+                const float* b2, void* hidden, void* y, int64_t ldy, int gelu_mode,
+                hipStream_t stream);
+
+// bf16 MFMA path.  `gather` (may be nullptr) holds, for every packed row, the row of x to
+// read (the dispatch permutation applied on load).  Returns SCMOE_ERR_ARG when the shape is
+// outside what the MFMA kernels cover (the caller then uses ffn_generic).
+int ffn_mfma_bf16(const void* x, int64_t ldx, const int32_t* gather, const int32_t* offsets,
+                  int max_rows, int E, int d, int F, const void* W1, const float* b1,
+                  const void* W2, const float* b2, void* hidden, void* y, int64_t ldy,
+                  int gelu_mode, hipStream_t stream);
+bool ffn_mfma_supported(int d, int F);
+
+}  // namespace scmoe

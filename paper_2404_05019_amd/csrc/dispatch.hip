@@ -1,0 +1,206 @@
+// Input encode (ScMoE paper Sec. 2.2): capacity-bounded stable permutation of token rows
+// into per-expert segments.  On one GPU this replaces "encode + All-to-All dispatch".
+//
+// Items are (token t, choice j) pairs in the order i = j*T + t, so every first choice is
+// ranked before any second choice.  The slot of an item is the number of earlier items of
+// the same expert.  Positions come from counting (ballot / popcount / prefix sums), never
+// from the arrival order of atomics, so the permutation is reproducible bit for bit.
+//
+//   hist : per block of 256 items, items per expert            -> blockhist[nblk, E]
+//   scan : exclusive prefix over blocks, counts, offsets       -> blockbase[nblk, E]
+//   rank : slot = blockbase + waves before + lanes before      -> dst_row, src_token
+//   rows : x_perm[r, :] = x[src_token[r], :] for r < offsets[E]
+#include "common.hpp"
+
+namespace scmoe {
+
+constexpr int DISP_BLOCK = 256;
+
+__device__ __forceinline__ int item_expert(const int32_t* __restrict__ expert_idx, int i, int n,
+                                           int T, int k, int E, int* t_out, int* j_out) {
+  if (i >= n) return -1;
+  const int j = i / T;
+  const int t = i - j * T;
+  *t_out = t;
+  *j_out = j;
+  const int e = expert_idx[static_cast<int64_t>(t) * k + j];
+  return (e >= 0 && e < E) ? e : -1;
+}
+
+__global__ __launch_bounds__(DISP_BLOCK) void dispatch_hist(const int32_t* __restrict__ expert_idx,
+                                                           int T, int k, int E,
+                                                           int32_t* __restrict__ blockhist) {
+  __shared__ int hist[SCMOE_MAX_EXPERTS];
+  const int tid = threadIdx.x;
+  if (tid < E) hist[tid] = 0;
+  __syncthreads();
+  int t, j;
+  const int e = item_expert(expert_idx, blockIdx.x * DISP_BLOCK + tid, T * k, T, k, E, &t, &j);
+  if (e >= 0) atomicAdd(&hist[e], 1);  // integer counts: the sum does not depend on order
+  __syncthreads();
+  if (tid < E) blockhist[static_cast<int64_t>(blockIdx.x) * E + tid] = hist[tid];
+}
+
+// One workgroup.  Thread e walks the blocks in order.
+__global__ __launch_bounds__(64) void dispatch_scan(const int32_t* __restrict__ blockhist, int nblk,
+                                                    int E, int capacity,
+                                                    int32_t* __restrict__ blockbase,
+                                                    int32_t* __restrict__ counts,
+                                                    int32_t* __restrict__ offsets) {
+  __shared__ int cnt[SCMOE_MAX_EXPERTS];
+  const int e = threadIdx.x;
+  if (e < E) {
+    int run = 0;
+    for (int b = 0; b < nblk; ++b) {
+      const int h = blockhist[static_cast<int64_t>(b) * E + e];
+      blockbase[static_cast<int64_t>(b) * E + e] = run;
+      run += h;
+    }
+    const int c = run < capacity ? run : capacity;
+    cnt[e] = c;
+    counts[e] = c;
+  }
+  __syncthreads();
+  if (e == 0) {
+    int run = 0;
+    for (int q = 0; q < E; ++q) {
+      offsets[q] = run;
+      run += cnt[q];
+    }
+    offsets[E] = run;
+  }
+}
+
+__global__ __launch_bounds__(DISP_BLOCK) void dispatch_rank(
+    const int32_t* __restrict__ expert_idx, int T, int k, int E, int capacity,
+    const int32_t* __restrict__ blockbase, const int32_t* __restrict__ offsets,
+    int32_t* __restrict__ dst_row, int32_t* __restrict__ src_token) {
+  __shared__ int wavecnt[DISP_BLOCK / 64][SCMOE_MAX_EXPERTS];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  for (int c = tid; c < (DISP_BLOCK / 64) * SCMOE_MAX_EXPERTS; c += DISP_BLOCK) (&wavecnt[0][0])[c] = 0;
+  __syncthreads();
+  int t = 0, j = 0;
+  const int e = item_expert(expert_idx, blockIdx.x * DISP_BLOCK + tid, T * k, T, k, E, &t, &j);
+  const bool valid = e >= 0;
+  // lanes of this wave that hold the same expert (an emulated "match any")
+  unsigned long long same = __ballot(valid);
+  for (int b = 0; (1 << b) < E; ++b) {
+    const unsigned long long bal = __ballot(valid && ((e >> b) & 1));
+    same &= ((e >> b) & 1) ? bal : ~bal;
+  }
+  const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  const int before = __popcll(same & below);
+  if (valid && before == 0) wavecnt[wave][e] = __popcll(same);
+  __syncthreads();
+  const int i = blockIdx.x * DISP_BLOCK + tid;
+  if (i < T * k) {
+    int out = -1;
+    if (valid) {
+      int slot = blockbase[static_cast<int64_t>(blockIdx.x) * E + e] + before;
+      for (int w = 0; w < wave; ++w) slot += wavecnt[w][e];
+      if (slot < capacity) {
+        out = offsets[e] + slot;
+        src_token[out] = t;
+      }
+    }
+    dst_row[static_cast<int64_t>(t) * k + j] = out;
+  }
+}
+
+// x_perm[r, :] = x[src_token[r], :], 16 bytes per lane, one wave per row.
+__global__ __launch_bounds__(256) void gather_rows(const unsigned char* __restrict__ x, int64_t ldx_bytes,
+                                                   const int32_t* __restrict__ src_token,
+                                                   const int32_t* __restrict__ offsets, int E,
+                                                   int row_bytes, unsigned char* __restrict__ x_perm,
+                                                   int64_t ldp_bytes) {
+  const int K = offsets[E];
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int nwaves = gridDim.x * (blockDim.x >> 6);
+  for (int r = wave; r < K; r += nwaves) {
+    const int src = src_token[r];
+    const unsigned char* s = x + static_cast<int64_t>(src) * ldx_bytes;
+    unsigned char* q = x_perm + static_cast<int64_t>(r) * ldp_bytes;
+    for (int c = lane * 16; c < row_bytes; c += 64 * 16 * 4) {
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c + u * 1024 < row_bytes) v[u] = *reinterpret_cast<const uint4*>(s + c + u * 1024);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (c + u * 1024 < row_bytes) *reinterpret_cast<uint4*>(q + c + u * 1024) = v[u];
+    }
+  }
+}
+
+static inline int disp_nblk(int T, int k) {
+  const int64_t n = static_cast<int64_t>(T) * k;
+  return static_cast<int>((n + DISP_BLOCK - 1) / DISP_BLOCK);
+}
+
+size_t dispatch_ws_bytes(int T, int E, int k) {
+  // blockhist + blockbase, each [nblk, E] int32, rounded up to 256 bytes
+  const size_t one = static_cast<size_t>(disp_nblk(T, k)) * static_cast<size_t>(E) * sizeof(int32_t);
+  return ((2 * one + 255) / 256) * 256;
+}
+
+int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, int T, int d, int E,
+             int k, int capacity, int32_t* counts, int32_t* offsets, int32_t* dst_row,
+             int32_t* src_token, void* x_perm, int64_t ld_perm, void* workspace, size_t ws_bytes,
+             hipStream_t stream) {
+  if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
+  if (T < 0 || E < 1 || E > SCMOE_MAX_EXPERTS || capacity < 0) return SCMOE_ERR_SHAPE;
+  if (k != 1 && k != 2) return SCMOE_ERR_ARG;
+  if (static_cast<int64_t>(T) * k > 0x7fffffffLL) return SCMOE_ERR_SHAPE;
+  if (!counts || !offsets) return SCMOE_ERR_NULL;
+  if (T > 0 && (!expert_idx || !dst_row || !src_token)) return SCMOE_ERR_NULL;
+  if (x_perm != nullptr) {
+    if (d <= 0 || (d % 8) != 0) return SCMOE_ERR_SHAPE;
+    if (T > 0 && !x) return SCMOE_ERR_NULL;
+    if (T > 0 && (!view_ok(x, ldx, d, dtype) || !view_ok(x_perm, ld_perm, d, dtype))) return SCMOE_ERR_SHAPE;
+  }
+  if (ws_bytes < dispatch_ws_bytes(T, E, k)) return SCMOE_ERR_WORKSPACE;
+  if (T > 0 && !workspace) return SCMOE_ERR_NULL;
+  const int nblk = disp_nblk(T, k);
+  int32_t* blockhist = static_cast<int32_t*>(workspace);
+  int32_t* blockbase = blockhist + static_cast<size_t>(nblk) * E;
+  if (nblk > 0)
+    hipLaunchKernelGGL(dispatch_hist, dim3(nblk), dim3(DISP_BLOCK), 0, stream, expert_idx, T, k, E, blockhist);
+  hipLaunchKernelGGL(dispatch_scan, dim3(1), dim3(64), 0, stream, blockhist, nblk, E, capacity, blockbase,
+                     counts, offsets);
+  if (nblk > 0) {
+    hipLaunchKernelGGL(dispatch_rank, dim3(nblk), dim3(DISP_BLOCK), 0, stream, expert_idx, T, k, E, capacity,
+                       blockbase, offsets, dst_row, src_token);
+    if (x_perm != nullptr) {
+      const int64_t max_rows = static_cast<int64_t>(T) * k;
+      int blocks = static_cast<int>((max_rows + 3) / 4);
+      if (blocks > 4096) blocks = 4096;
+      const int eb = elem_bytes(dtype);
+      hipLaunchKernelGGL(gather_rows, dim3(blocks), dim3(256), 0, stream, static_cast<const unsigned char*>(x),
+                         ldx * eb, src_token, offsets, E, d * eb, static_cast<unsigned char*>(x_perm),
+                         ld_perm * eb);
+    }
+  }
+  return launch_status();
+}
+
+}  // namespace scmoe
+
+extern "C" int scmoe_dispatch_workspace_bytes(int32_t T, int32_t E, int32_t k, size_t* out) {
+  if (!out) return SCMOE_ERR_NULL;
+  if (T < 0 || E < 1 || E > SCMOE_MAX_EXPERTS) return SCMOE_ERR_SHAPE;
+  if (k != 1 && k != 2) return SCMOE_ERR_ARG;
+  *out = scmoe::dispatch_ws_bytes(T, E, k);
+  return SCMOE_OK;
+}
+
+extern "C" int scmoe_dispatch(const void* x, int64_t ldx, int32_t dtype, const int32_t* expert_idx,
+                              int32_t T, int32_t d, int32_t E, int32_t k, int32_t capacity,
+                              int32_t* counts, int32_t* offsets, int32_t* dst_row,
+                              int32_t* src_token, void* x_perm, int64_t ld_perm, void* workspace,
+                              size_t ws_bytes, void* stream) {
+  return scmoe::dispatch(x, ldx, dtype, expert_idx, T, d, E, k, capacity, counts, offsets, dst_row,
+                         src_token, x_perm, ld_perm, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+}

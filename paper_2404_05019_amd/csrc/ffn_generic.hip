@@ -1,0 +1,123 @@
+// Expert computation (ScMoE paper Eq. (1); experts are two-layer MLPs, Sec. 2.1) for any
+// shape and both storage types: a plain LDS-tiled grouped GEMM on the vector ALUs with fp32
+// accumulation.  It is the fp32 path and the fallback for bf16 shapes the MFMA kernels do
+// not cover; the bf16 hot path lives in ffn_mfma.hip.
+//
+//   C[r, n] = act( sum_k A[r, k] * W[e, n, k] + bias[e, n] )   for r in segment e
+#include "common.hpp"
+
+namespace scmoe {
+
+constexpr int GT = 64;   // tile edge (rows and columns)
+constexpr int GK = 16;   // depth of one LDS stage
+
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const unsigned char* p, int64_t i) {
+  if (BF16) return bf16_to_f32(reinterpret_cast<const uint16_t*>(p)[i]);
+  return reinterpret_cast<const float*>(p)[i];
+}
+
+template <bool BF16>
+__device__ __forceinline__ void store_elem(unsigned char* p, int64_t i, float v) {
+  if (BF16) reinterpret_cast<uint16_t*>(p)[i] = f32_to_bf16(v);
+  else reinterpret_cast<float*>(p)[i] = v;
+}
+
+template <bool BF16, bool ACT>
+__global__ __launch_bounds__(256) void ffn_generic_kernel(
+    const unsigned char* __restrict__ A, int64_t lda, const int32_t* __restrict__ offsets, int E,
+    int N, int Kd, const unsigned char* __restrict__ W, const float* __restrict__ bias,
+    unsigned char* __restrict__ C, int64_t ldc, int gelu_mode) {
+  __shared__ float As[GK][GT + 1];
+  __shared__ float Bs[GK][GT + 1];
+  // which expert segment does this row tile belong to?
+  int mt = blockIdx.x, e = 0, row0 = 0, row_end = 0;
+  bool found = false;
+  for (e = 0; e < E; ++e) {
+    const int s = offsets[e], c = offsets[e + 1] - s;
+    const int nt = (c + GT - 1) / GT;
+    if (mt < nt) {
+      row0 = s + mt * GT;
+      row_end = s + c;
+      found = true;
+      break;
+    }
+    mt -= nt;
+  }
+  if (!found) return;
+  const int n0 = blockIdx.y * GT;
+  const unsigned char* We = W + static_cast<int64_t>(e) * N * Kd * (BF16 ? 2 : 4);
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
+
+  for (int k0 = 0; k0 < Kd; k0 += GK) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int idx = tid + q * 256;
+      const int r = idx >> 4, kk = idx & 15;
+      const int row = row0 + r, kg = k0 + kk, n = n0 + r;
+      As[kk][r] = (row < row_end && kg < Kd) ? load_elem<BF16>(A, static_cast<int64_t>(row) * lda + kg) : 0.0f;
+      Bs[kk][r] = (n < N && kg < Kd) ? load_elem<BF16>(We, static_cast<int64_t>(n) * Kd + kg) : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < GK; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = row0 + ty * 4 + i;
+    if (row >= row_end) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= N) continue;
+      float v = acc[i][j];
+      if (bias != nullptr) v += bias[static_cast<int64_t>(e) * N + n];
+      if (ACT) v = gelu_f32(v, gelu_mode);
+      store_elem<BF16>(C, static_cast<int64_t>(row) * ldc + n, v);
+    }
+  }
+}
+
+int ffn_generic(const void* x, int64_t ldx, int dtype, const int32_t* offsets, int max_rows, int E,
+                int d, int F, const void* W1, const float* b1, const void* W2, const float* b2,
+                void* hidden, void* y, int64_t ldy, int gelu_mode, hipStream_t stream) {
+  const int mt = (max_rows + GT - 1) / GT + E;  // upper bound on row tiles over all segments
+  const unsigned char* xb = static_cast<const unsigned char*>(x);
+  const unsigned char* w1 = static_cast<const unsigned char*>(W1);
+  const unsigned char* w2 = static_cast<const unsigned char*>(W2);
+  unsigned char* hb = static_cast<unsigned char*>(hidden);
+  unsigned char* yb = static_cast<unsigned char*>(y);
+  dim3 block(256);
+  dim3 g1(mt, (F + GT - 1) / GT), g2(mt, (d + GT - 1) / GT);
+  if (dtype == SCMOE_BF16) {
+    hipLaunchKernelGGL((ffn_generic_kernel<true, true>), g1, block, 0, stream, xb, ldx, offsets, E, F, d, w1, b1,
+                       hb, static_cast<int64_t>(F), gelu_mode);
+    hipLaunchKernelGGL((ffn_generic_kernel<true, false>), g2, block, 0, stream, hb, static_cast<int64_t>(F),
+                       offsets, E, d, F, w2, b2, yb, ldy, gelu_mode);
+  } else {
+    hipLaunchKernelGGL((ffn_generic_kernel<false, true>), g1, block, 0, stream, xb, ldx, offsets, E, F, d, w1, b1,
+                       hb, static_cast<int64_t>(F), gelu_mode);
+    hipLaunchKernelGGL((ffn_generic_kernel<false, false>), g2, block, 0, stream, hb, static_cast<int64_t>(F),
+                       offsets, E, d, F, w2, b2, yb, ldy, gelu_mode);
+  }
+  return launch_status();
+}
+
+}  // namespace scmoe

@@ -1,0 +1,359 @@
+// Expert computation (ScMoE paper Eq. (1); experts are two-layer MLPs, Sec. 2.1) in bf16
+// on the CDNA4 matrix cores: a grouped GEMM over variable-length expert segments.
+//
+//   C[r, n] = act( sum_k A[row(r), k] * W[e, n, k] + bias[e, n] ),  r in segment e
+//
+// Both operands are K-contiguous ([rows, K] activations, [N, K] weights), which is the
+// layout v_mfma_f32_32x32x16_bf16 wants: each lane feeds 8 consecutive k of one row.
+//
+// Design (gfx950):
+//  * A workgroup owns a BM x BN output tile of ONE expert.  Tiles are enumerated on the
+//    device from offsets[] (no host round trip); surplus workgroups exit at once.
+//  * Global -> LDS copies use the direct-to-LDS form of the global load (16 bytes per
+//    lane, no VGPR staging).  Such a load writes 1 KiB of consecutive LDS per wave, so the
+//    bank-conflict swizzle is applied on the global side: the lane that fills LDS slot
+//    (row, c) fetches k-chunk  c ^ swz(row)  of that row.
+//  * LDS is double buffered: the loads of k-tile t+1 are in flight while the waves issue
+//    the MFMAs of k-tile t; one workgroup barrier per k-tile.
+//  * The MFMA is issued with the weight fragment as its first operand, so a lane ends up
+//    holding 4 consecutive output columns of one row and stores them as one 8-byte piece.
+//  * Workgroup ids are remapped so that each XCD (ids congruent mod 8 land on one XCD and
+//    share its L2) walks a compact block of neighbouring tiles.
+//  * Rows can be gathered on load through an index array (the dispatch permutation), which
+//    lets the layer skip materialising the permuted activations.
+#include "common.hpp"
+
+#include <stdlib.h>
+
+namespace scmoe {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+#define SCMOE_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define SCMOE_GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// XOR swizzles of the 16-byte chunk index inside an LDS row.  Chosen so that 8 or 16
+// consecutive rows reading the same logical chunk fall into distinct bank groups.
+template <int CPR>
+__host__ __device__ constexpr int swz(int r) {
+  return CPR == 8 ? ((r + (r >> 3)) & 7) : (((r >> 1) + (r >> 3)) & 3);
+}
+
+struct GemmArgs {
+  const unsigned char* A;   // activations, bf16 [rows, Kd]
+  int64_t lda;              // row stride of A in elements
+  const int32_t* gather;    // row r of the packed order reads A[gather[r]]; nullptr = identity
+  const int32_t* offsets;   // [E + 1] segment starts, device
+  const unsigned char* W;   // bf16 [E, N, Kd]
+  const float* bias;        // [E, N] or nullptr
+  unsigned char* C;         // bf16 [rows, N], row stride ldc
+  int64_t ldc;
+  int E, N, Kd;
+  int mtb;                  // upper bound on row tiles, multiple of the raster group
+  int nt;                   // column tiles
+  int chunk;                // logical tiles per XCD
+  int gelu_mode;
+};
+
+// erf-form GELU for the bf16 epilogue: erf(v / sqrt 2) ~ v * P(v^2) on |v| <= 3 sqrt 2,
+// saturated outside (degree-8 minimax fit; |error of GELU| < 6e-5, far below the bf16
+// rounding of the stored value).  13 VALU operations, no transcendental.
+__device__ __forceinline__ float gelu_erf_fast(float v) {
+  const float vc = __builtin_amdgcn_fmed3f(v, -4.2426405f, 4.2426405f);
+  const float u = vc * vc;
+  float p = 1.1253472459449299e-10f;
+  p = fmaf(p, u, -1.0743693046322278e-08f);
+  p = fmaf(p, u, 4.5365794676399673e-07f);
+  p = fmaf(p, u, -1.1292409908492118e-05f);
+  p = fmaf(p, u, 0.0001871810673037544f);
+  p = fmaf(p, u, -0.002218799665570259f);
+  p = fmaf(p, u, 0.019636236131191254f);
+  p = fmaf(p, u, -0.1326938420534134f);
+  p = fmaf(p, u, 0.7978062629699707f);
+  const float e = p * vc;
+  const float h = 0.5f * v;
+  return fmaf(h, e, h);
+}
+
+__device__ __forceinline__ float gelu_tanh_fast(float v) {
+  // 0.5 v (1 + tanh u) == v / (1 + exp(-2u))
+  const float u2 = -1.5957691216057308f * (v + 0.044715f * v * v * v);
+  return v * __frcp_rn(1.0f + __expf(u2));
+}
+
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
+  f32x2_t f = {a, b};
+  bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_>
+struct TileCfg {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+  static constexpr int WAVES = WM * WN, THREADS = 64 * WAVES;
+  static constexpr int TM = BM / WM, TN = BN / WN;       // wave tile
+  static constexpr int MI = TM / 32, NJ = TN / 32;       // 32x32 MFMA tiles per wave
+  static constexpr int RB = BK * 2;                      // bytes of one LDS row
+  static constexpr int CPR = RB / 16;                    // 16-byte chunks per row
+  static constexpr int RPL = 64 / CPR;                   // rows filled by one wave-wide load
+  static constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB, STAGE = A_BYTES + B_BYTES;
+  static constexpr int A_PER_WAVE = BM / RPL / WAVES, B_PER_WAVE = BN / RPL / WAVES;
+  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int GM = 4;                           // row tiles per raster group
+  static_assert(BM % (RPL * WAVES) == 0 && BN % (RPL * WAVES) == 0, "loads must divide evenly");
+  static_assert(TM % 32 == 0 && TN % 32 == 0 && (BK == 32 || BK == 64), "tile shape");
+};
+
+template <class CFG, bool ACT>
+__global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmArgs p) {
+  constexpr int BM = CFG::BM, BN = CFG::BN, BK = CFG::BK, RB = CFG::RB, CPR = CFG::CPR;
+  constexpr int MI = CFG::MI, NJ = CFG::NJ, STAGE = CFG::STAGE, A_BYTES = CFG::A_BYTES;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // ---- which tile? ----------------------------------------------------------------------
+  const int bid = blockIdx.x;
+  const int L = (bid & 7) * p.chunk + (bid >> 3);
+  if (L >= p.mtb * p.nt) return;
+  const int grp = L / (CFG::GM * p.nt);
+  const int rem = L - grp * CFG::GM * p.nt;
+  int mt = grp * CFG::GM + rem % CFG::GM;
+  const int n0 = (rem / CFG::GM) * BN;
+  int e = 0, row0 = 0, row_end = 0;
+  bool found = false;
+  for (e = 0; e < p.E; ++e) {
+    const int s = p.offsets[e];
+    const int c = p.offsets[e + 1] - s;
+    const int ntile = (c + BM - 1) / BM;
+    if (mt < ntile) {
+      row0 = s + mt * BM;
+      row_end = s + c;
+      found = true;
+      break;
+    }
+    mt -= ntile;
+  }
+  if (!found) return;
+
+  // ---- per-lane source addresses of the direct-to-LDS loads -------------------------------
+  const unsigned char* We = p.W + static_cast<int64_t>(e) * p.N * p.Kd * 2;
+  const unsigned char* aptr[CFG::A_PER_WAVE];
+  const unsigned char* bptr[CFG::B_PER_WAVE];
+#pragma unroll
+  for (int i = 0; i < CFG::A_PER_WAVE; ++i) {
+    const int row = (wave * CFG::A_PER_WAVE + i) * CFG::RPL + lane / CPR;
+    const int kc = (lane % CPR) ^ swz<CPR>(row);
+    int m = row0 + row;
+    if (m > row_end - 1) m = row_end - 1;        // rows past the segment re-read its last row
+    const int64_t src = p.gather ? p.gather[m] : m;
+    aptr[i] = p.A + src * p.lda * 2 + kc * 16;
+  }
+#pragma unroll
+  for (int i = 0; i < CFG::B_PER_WAVE; ++i) {
+    const int row = (wave * CFG::B_PER_WAVE + i) * CFG::RPL + lane / CPR;
+    const int kc = (lane % CPR) ^ swz<CPR>(row);
+    int n = n0 + row;
+    if (n > p.N - 1) n = p.N - 1;
+    bptr[i] = We + static_cast<int64_t>(n) * p.Kd * 2 + kc * 16;
+  }
+
+  auto issue_loads = [&](int kt, int stage) {
+    unsigned char* sa = smem + stage * STAGE + wave * CFG::A_PER_WAVE * 1024;
+    unsigned char* sb = smem + stage * STAGE + A_BYTES + wave * CFG::B_PER_WAVE * 1024;
+#pragma unroll
+    for (int i = 0; i < CFG::A_PER_WAVE; ++i)
+      __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(aptr[i] + static_cast<int64_t>(kt) * RB),
+                                       SCMOE_LDS_PTR(sa + i * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < CFG::B_PER_WAVE; ++i)
+      __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(bptr[i] + static_cast<int64_t>(kt) * RB),
+                                       SCMOE_LDS_PTR(sb + i * 1024), 16, 0, 0);
+  };
+
+  // ---- fragment read offsets ---------------------------------------------------------------
+  const int wave_m = wave / CFG::WN, wave_n = wave % CFG::WN;
+  const int lr = lane & 31, lh = lane >> 5;
+  int xoff[MI], woff[NJ];   // byte offset of (row, chunk lh) for k16-step 0, swizzled
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int row = wave_m * CFG::TM + i * 32 + lr;
+    xoff[i] = row * RB + ((lh ^ swz<CPR>(row)) << 4);
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = wave_n * CFG::TN + j * 32 + lr;
+    woff[j] = A_BYTES + row * RB + ((lh ^ swz<CPR>(row)) << 4);
+  }
+
+  f32x16_t acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  const int nk = p.Kd / BK;
+  issue_loads(0, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int stage = kt & 1;
+    // this wave's loads of k-tile kt have landed; after the barrier everybody's have, and
+    // nobody still reads the other stage (it was consumed in iteration kt-1)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt + 1 < nk) issue_loads(kt + 1, stage ^ 1);
+    const unsigned char* st = smem + stage * STAGE;
+#pragma unroll
+    for (int s = 0; s < BK / 16; ++s) {
+      // k16-step s reads chunks 2s and 2s+1: XOR on the swizzled chunk index
+      bf16x8_t xf[MI], wf[NJ];
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+        xf[i] = *reinterpret_cast<const bf16x8_t*>(st + (xoff[i] ^ (s << 5)));
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        wf[j] = *reinterpret_cast<const bf16x8_t*>(st + (woff[j] ^ (s << 5)));
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // ---- epilogue: bias, activation, bf16, 8-byte stores ----------------------------------
+  // acc[i][j][v] is output row (lane & 31) of row-subtile i and column
+  // 8*(v/4) + 4*(lane/32) + v%4 of column-subtile j.
+  const float* bias_e = p.bias ? p.bias + static_cast<int64_t>(e) * p.N : nullptr;
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int m = row0 + wave_m * CFG::TM + i * 32 + lr;
+    if (m >= row_end) continue;
+    unsigned char* crow = p.C + static_cast<int64_t>(m) * p.ldc * 2;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n = n0 + wave_n * CFG::TN + j * 32 + 8 * g + 4 * lh;
+        if (n >= p.N) continue;
+        float v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = acc[i][j][4 * g + q];
+        if (bias_e) {
+          const float4 b = *reinterpret_cast<const float4*>(bias_e + n);
+          v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
+        }
+        if (ACT) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            v[q] = (p.gelu_mode == SCMOE_GELU_TANH) ? gelu_tanh_fast(v[q]) : gelu_erf_fast(v[q]);
+        }
+        uint2 o;
+        o.x = cvt_pk_bf16(v[0], v[1]);
+        o.y = cvt_pk_bf16(v[2], v[3]);
+        *reinterpret_cast<uint2*>(crow + static_cast<int64_t>(n) * 2) = o;
+      }
+    }
+  }
+}
+
+// ---- host side --------------------------------------------------------------------------------
+
+using CfgA = TileCfg<256, 256, 64, 2, 4>;   // 8 waves, 128 KiB LDS, one workgroup per CU
+using CfgB = TileCfg<256, 256, 32, 2, 4>;   // 8 waves, 64 KiB LDS
+using CfgC = TileCfg<256, 128, 32, 2, 2>;   // 4 waves, 48 KiB LDS, two workgroups per CU
+
+// Tile configuration in use: set by scmoe_set_gemm_variant, else SCMOE_GEMM_VARIANT, else 0.
+static int g_variant = -1;
+constexpr int NUM_VARIANTS = 3;
+
+static int gemm_variant() {
+  if (g_variant < 0) {
+    const char* s = getenv("SCMOE_GEMM_VARIANT");
+    int v = s ? atoi(s) : 0;
+    g_variant = (v < 0 || v >= NUM_VARIANTS) ? 0 : v;
+  }
+  return g_variant;
+}
+
+int set_gemm_variant(int v) {
+  if (v < 0 || v >= NUM_VARIANTS) return SCMOE_ERR_ARG;
+  g_variant = v;
+  return SCMOE_OK;
+}
+
+bool ffn_mfma_supported(int d, int F) { return d > 0 && F > 0 && (d % 64) == 0 && (F % 64) == 0; }
+
+template <class CFG, bool ACT>
+static int launch_gemm(GemmArgs a, int max_rows, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<CFG, ACT>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, CFG::LDS_BYTES);
+    if (err != hipSuccess) return hip_fail(err);
+    attr_set = true;
+  }
+  int mtb = max_rows / CFG::BM + a.E;
+  mtb = ((mtb + CFG::GM - 1) / CFG::GM) * CFG::GM;
+  a.mtb = mtb;
+  a.nt = (a.N + CFG::BN - 1) / CFG::BN;
+  const int total = a.mtb * a.nt;
+  a.chunk = (total + 7) / 8;
+  hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT>), dim3(8 * a.chunk), dim3(CFG::THREADS), CFG::LDS_BYTES,
+                     stream, a);
+  return launch_status();
+}
+
+template <bool ACT>
+static int launch_variant(const GemmArgs& a, int max_rows, hipStream_t stream) {
+  switch (gemm_variant()) {
+    case 1: return launch_gemm<CfgB, ACT>(a, max_rows, stream);
+    case 2: return launch_gemm<CfgC, ACT>(a, max_rows, stream);
+    default: return launch_gemm<CfgA, ACT>(a, max_rows, stream);
+  }
+}
+
+int ffn_mfma_bf16(const void* x, int64_t ldx, const int32_t* gather, const int32_t* offsets,
+                  int max_rows, int E, int d, int F, const void* W1, const float* b1, const void* W2,
+                  const float* b2, void* hidden, void* y, int64_t ldy, int gelu_mode,
+                  hipStream_t stream) {
+  if (!ffn_mfma_supported(d, F)) return SCMOE_ERR_ARG;
+  if (max_rows <= 0) return SCMOE_OK;
+  GemmArgs g1{};
+  g1.A = static_cast<const unsigned char*>(x);
+  g1.lda = ldx;
+  g1.gather = gather;
+  g1.offsets = offsets;
+  g1.W = static_cast<const unsigned char*>(W1);
+  g1.bias = b1;
+  g1.C = static_cast<unsigned char*>(hidden);
+  g1.ldc = F;
+  g1.E = E;
+  g1.N = F;
+  g1.Kd = d;
+  g1.gelu_mode = gelu_mode;
+  int st = launch_variant<true>(g1, max_rows, stream);
+  if (st != SCMOE_OK) return st;
+  GemmArgs g2{};
+  g2.A = static_cast<const unsigned char*>(hidden);
+  g2.lda = F;
+  g2.gather = nullptr;
+  g2.offsets = offsets;
+  g2.W = static_cast<const unsigned char*>(W2);
+  g2.bias = b2;
+  g2.C = static_cast<unsigned char*>(y);
+  g2.ldc = ldy;
+  g2.E = E;
+  g2.N = d;
+  g2.Kd = F;
+  g2.gelu_mode = gelu_mode;
+  return launch_variant<false>(g2, max_rows, stream);
+}
+
+}  // namespace scmoe

@@ -1,0 +1,324 @@
+// C-ABI entry points that are not a single kernel: status text, capacity, workspace sizes,
+// the expert FFN dispatcher, and the layer orchestration of ScMoE (paper Eq. (7), Sec. 3.2)
+// and of the standard top-k MoE layer (Eq. (1)-(4)).
+#include "common.hpp"
+
+#include <math.h>
+
+namespace scmoe {
+
+thread_local int g_last_hip_error = 0;
+
+int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const float* bias, int T,
+              int d, int E, int k, int normalize, int32_t* idx, float* gw, float* probs,
+              hipStream_t stream);
+size_t dispatch_ws_bytes(int T, int E, int k);
+int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, int T, int d, int E,
+             int k, int capacity, int32_t* counts, int32_t* offsets, int32_t* dst_row,
+             int32_t* src_token, void* x_perm, int64_t ld_perm, void* workspace, size_t ws_bytes,
+             hipStream_t stream);
+int combine(const void* y_perm, int64_t ldyp, int dtype, const int32_t* dst_row, const float* gate_w,
+            int T, int d, int k, const void* base, int64_t ldbase, const void* residual,
+            int64_t ldres, const float* coef, void* y, int64_t ldy, hipStream_t stream);
+int coef_gate(const void* x, int64_t ldx, int dtype, const float* Wcg, int mode, int T, int d,
+              float* coef, hipStream_t stream);
+
+static inline size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+// Rows the packed buffers must hold: min(T*k, E*C) without overflow.
+static inline int64_t packed_rows(int T, int E, int k, int capacity) {
+  const int64_t items = static_cast<int64_t>(T) * k;
+  const int64_t cap = static_cast<int64_t>(E) * capacity;
+  return items < cap ? items : cap;
+}
+
+static int check_desc(const scmoe_desc* D, int kmin, int kmax) {
+  if (!D) return SCMOE_ERR_NULL;
+  if (!dtype_ok(D->dtype)) return SCMOE_ERR_DTYPE;
+  if (D->T < 0 || D->d <= 0 || D->F <= 0 || (D->d % 8) || (D->F % 8) || D->E < 1 ||
+      D->E > SCMOE_MAX_EXPERTS || D->capacity < 0)
+    return SCMOE_ERR_SHAPE;
+  if (static_cast<int64_t>(D->T) * 2 > 0x7fffffffLL) return SCMOE_ERR_SHAPE;
+  if (D->k < kmin || D->k > kmax) return SCMOE_ERR_ARG;
+  if (D->k == 2 && D->E < 2) return SCMOE_ERR_SHAPE;
+  if (D->gelu_mode != SCMOE_GELU_ERF && D->gelu_mode != SCMOE_GELU_TANH) return SCMOE_ERR_ARG;
+  if (D->normalize != 0 && D->normalize != 1) return SCMOE_ERR_ARG;
+  if (D->cg_mode < SCMOE_CG_NONE || D->cg_mode > SCMOE_CG_2) return SCMOE_ERR_ARG;
+  return SCMOE_OK;
+}
+
+// Carves the layer workspace.  Every piece starts on a 256-byte boundary.
+struct LayerWs {
+  int32_t* expert_idx; float* gate_w; int32_t* counts; int32_t* offsets; int32_t* dst_row;
+  int32_t* src_token; int32_t* offsets_shared; float* coef; void* disp_ws; size_t disp_bytes;
+  void* x_perm; void* hidden; void* y_perm; void* hidden_s; void* s;
+  size_t total;
+};
+
+static LayerWs carve(const scmoe_desc* D, void* base, bool shared) {
+  LayerWs w{};
+  size_t off = 0;
+  unsigned char* b = static_cast<unsigned char*>(base);
+  auto take = [&](size_t bytes) {
+    void* p = b ? b + off : nullptr;
+    off += align256(bytes);
+    return p;
+  };
+  const size_t items = static_cast<size_t>(D->T) * D->k;
+  const size_t rows = static_cast<size_t>(packed_rows(D->T, D->E, D->k, D->capacity));
+  const size_t eb = elem_bytes(D->dtype);
+  w.expert_idx = static_cast<int32_t*>(take(items * 4));
+  w.gate_w = static_cast<float*>(take(items * 4));
+  w.counts = static_cast<int32_t*>(take(static_cast<size_t>(D->E) * 4));
+  w.offsets = static_cast<int32_t*>(take(static_cast<size_t>(D->E + 1) * 4));
+  w.dst_row = static_cast<int32_t*>(take(items * 4));
+  w.src_token = static_cast<int32_t*>(take(rows * 4));
+  w.offsets_shared = static_cast<int32_t*>(take(8));
+  w.coef = static_cast<float*>(take(D->cg_mode ? static_cast<size_t>(D->T) * 8 : 0));
+  w.disp_bytes = dispatch_ws_bytes(D->T, D->E, D->k);
+  w.disp_ws = take(w.disp_bytes);
+  w.x_perm = take(rows * D->d * eb);
+  w.hidden = take(rows * D->F * eb);
+  w.y_perm = take(rows * D->d * eb);
+  if (shared) {
+    w.hidden_s = take(static_cast<size_t>(D->T) * D->F * eb);
+    w.s = take(static_cast<size_t>(D->T) * D->d * eb);
+  }
+  w.total = off;
+  return w;
+}
+
+__global__ void set_pair(int32_t* p, int a, int b) {
+  if (threadIdx.x == 0) {
+    p[0] = a;
+    p[1] = b;
+  }
+}
+
+// FFN over segments: MFMA path for bf16 shapes it covers, else the generic kernel.
+static int expert_ffn_any(const void* x, int64_t ldx, int dtype, const int32_t* gather,
+                          const int32_t* offsets, int max_rows, int E, int d, int F, const void* W1,
+                          const float* b1, const void* W2, const float* b2, void* hidden, void* y,
+                          int64_t ldy, int gelu_mode, hipStream_t stream) {
+  if (max_rows <= 0) return SCMOE_OK;
+  if (dtype == SCMOE_BF16 && ffn_mfma_supported(d, F))
+    return ffn_mfma_bf16(x, ldx, gather, offsets, max_rows, E, d, F, W1, b1, W2, b2, hidden, y, ldy,
+                         gelu_mode, stream);
+  if (gather != nullptr) return SCMOE_ERR_ARG;  // the generic kernel reads packed rows only
+  return ffn_generic(x, ldx, dtype, offsets, max_rows, E, d, F, W1, b1, W2, b2, hidden, y, ldy,
+                     gelu_mode, stream);
+}
+
+static bool gather_on_load(const scmoe_desc* D) {
+  return D->dtype == SCMOE_BF16 && ffn_mfma_supported(D->d, D->F);
+}
+
+// Fork/join events of the two-stream layer call: one pair per host thread and device.
+struct EventPair { hipEvent_t fork = nullptr, join = nullptr; };
+static int get_events(EventPair** out) {
+  constexpr int MAXDEV = 64;
+  static thread_local EventPair pairs[MAXDEV];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e);
+  if (dev < 0 || dev >= MAXDEV) return SCMOE_ERR_ARG;
+  EventPair& p = pairs[dev];
+  if (!p.fork) {
+    e = hipEventCreateWithFlags(&p.fork, hipEventDisableTiming);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipEventCreateWithFlags(&p.join, hipEventDisableTiming);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  *out = &p;
+  return SCMOE_OK;
+}
+
+#define SCMOE_TRY(expr)            \
+  do {                             \
+    int st__ = (expr);             \
+    if (st__ != SCMOE_OK) return st__; \
+  } while (0)
+
+static int copy_routing(const scmoe_desc* D, const LayerWs& w, const scmoe_routing_out* r,
+                        hipStream_t stream) {
+  if (!r || D->T == 0) return SCMOE_OK;
+  const size_t items = static_cast<size_t>(D->T) * D->k;
+  const size_t rows = static_cast<size_t>(packed_rows(D->T, D->E, D->k, D->capacity));
+  struct { void* dst; const void* src; size_t bytes; } cp[6] = {
+      {r->expert_idx, w.expert_idx, items * 4}, {r->gate_w, w.gate_w, items * 4},
+      {r->counts, w.counts, static_cast<size_t>(D->E) * 4},
+      {r->offsets, w.offsets, static_cast<size_t>(D->E + 1) * 4},
+      {r->dst_row, w.dst_row, items * 4}, {r->src_token, w.src_token, rows * 4}};
+  for (auto& c : cp) {
+    if (c.dst && c.bytes) {
+      hipError_t e = hipMemcpyAsync(c.dst, c.src, c.bytes, hipMemcpyDeviceToDevice, stream);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+  }
+  return SCMOE_OK;
+}
+
+// gate -> encode -> experts on `stream`; leaves y_perm, dst_row, gate_w in the workspace.
+static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const scmoe_weights* W,
+                        const LayerWs& w, hipStream_t stream) {
+  SCMOE_TRY(gate_topk(x, ldx, D->dtype, W->W_g, W->bias, D->T, D->d, D->E, D->k, D->normalize,
+                      w.expert_idx, w.gate_w, nullptr, stream));
+  const bool gol = gather_on_load(D);
+  SCMOE_TRY(dispatch(x, ldx, D->dtype, w.expert_idx, D->T, D->d, D->E, D->k, D->capacity, w.counts,
+                     w.offsets, w.dst_row, w.src_token, gol ? nullptr : w.x_perm, D->d, w.disp_ws,
+                     w.disp_bytes, stream));
+  const int rows = static_cast<int>(packed_rows(D->T, D->E, D->k, D->capacity));
+  if (gol)
+    return expert_ffn_any(x, ldx, D->dtype, w.src_token, w.offsets, rows, D->E, D->d, D->F, W->W1, W->b1,
+                          W->W2, W->b2, w.hidden, w.y_perm, D->d, D->gelu_mode, stream);
+  return expert_ffn_any(w.x_perm, D->d, D->dtype, nullptr, w.offsets, rows, D->E, D->d, D->F, W->W1,
+                        W->b1, W->W2, W->b2, w.hidden, w.y_perm, D->d, D->gelu_mode, stream);
+}
+
+}  // namespace scmoe
+
+using namespace scmoe;
+
+extern "C" const char* scmoe_status_string(int status) {
+  switch (status) {
+    case SCMOE_OK: return "ok";
+    case SCMOE_ERR_NULL: return "a required pointer is NULL";
+    case SCMOE_ERR_SHAPE: return "size, stride or alignment outside the contract";
+    case SCMOE_ERR_DTYPE: return "unknown dtype";
+    case SCMOE_ERR_WORKSPACE: return "workspace too small";
+    case SCMOE_ERR_HIP: return "HIP call failed (see scmoe_last_hip_error)";
+    case SCMOE_ERR_ARG: return "unsupported option value";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int scmoe_last_hip_error(void) { return g_last_hip_error; }
+
+namespace scmoe { int set_gemm_variant(int v); }
+extern "C" int scmoe_set_gemm_variant(int32_t variant) { return scmoe::set_gemm_variant(variant); }
+
+extern "C" int scmoe_capacity(int32_t T, int32_t E, int32_t k, double cf, int32_t* C) {
+  if (!C) return SCMOE_ERR_NULL;
+  if (T < 0 || E < 1 || k < 1 || !(cf >= 0.0)) return SCMOE_ERR_SHAPE;
+  const long double v = static_cast<long double>(cf) * k * T / E;
+  const long double r = nearbyintl(v);
+  const long double tol = 1e-9L * (fabsl(v) > 1.0L ? fabsl(v) : 1.0L);
+  const long double c = (fabsl(v - r) <= tol) ? r : ceill(v);
+  if (c > 2147483647.0L) return SCMOE_ERR_SHAPE;
+  *C = static_cast<int32_t>(c);
+  return SCMOE_OK;
+}
+
+extern "C" int scmoe_expert_ffn(const void* x_perm, int64_t ld_perm, int32_t dtype,
+                                const int32_t* offsets, int32_t max_rows, int32_t E, int32_t d,
+                                int32_t F, const void* W1, const float* b1, const void* W2,
+                                const float* b2, void* hidden, void* y_perm, int64_t ldy,
+                                int32_t gelu_mode, void* stream) {
+  if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
+  if (max_rows < 0 || E < 1 || d <= 0 || F <= 0 || (d % 8) || (F % 8)) return SCMOE_ERR_SHAPE;
+  if (gelu_mode != SCMOE_GELU_ERF && gelu_mode != SCMOE_GELU_TANH) return SCMOE_ERR_ARG;
+  if (max_rows == 0) return SCMOE_OK;
+  if (!x_perm || !offsets || !W1 || !W2 || !hidden || !y_perm) return SCMOE_ERR_NULL;
+  if (!view_ok(x_perm, ld_perm, d, dtype) || !view_ok(y_perm, ldy, d, dtype) || !aligned16(hidden) ||
+      !aligned16(W1) || !aligned16(W2))
+    return SCMOE_ERR_SHAPE;
+  if ((b1 && !aligned16(b1)) || (b2 && !aligned16(b2))) return SCMOE_ERR_SHAPE;
+  return expert_ffn_any(x_perm, ld_perm, dtype, nullptr, offsets, max_rows, E, d, F, W1, b1, W2, b2,
+                        hidden, y_perm, ldy, gelu_mode, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out) {
+  if (!out) return SCMOE_ERR_NULL;
+  SCMOE_TRY(check_desc(desc, 1, 2));
+  // sized for the shared-expert form; the standard layer uses a prefix of it
+  *out = carve(desc, nullptr, true).total;
+  return SCMOE_OK;
+}
+
+static int check_weights(const scmoe_desc* D, const scmoe_weights* W, bool shared) {
+  if (!W) return SCMOE_ERR_NULL;
+  if (!W->W_g || !W->W1 || !W->W2) return SCMOE_ERR_NULL;
+  if (shared && (!W->W1s || !W->W2s)) return SCMOE_ERR_NULL;
+  if (shared && D->cg_mode != SCMOE_CG_NONE && !W->W_cg) return SCMOE_ERR_NULL;
+  const void* ptrs[] = {W->W1, W->W2, W->b1, W->b2, shared ? W->W1s : nullptr,
+                        shared ? W->W2s : nullptr, shared ? W->b1s : nullptr, shared ? W->b2s : nullptr};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return SCMOE_ERR_SHAPE;
+  return SCMOE_OK;
+}
+
+extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int64_t ld_prev,
+                                   const void* x_cur, int64_t ld_cur, const scmoe_weights* W,
+                                   const void* residual, int64_t ldres, void* y, int64_t ldy,
+                                   const scmoe_routing_out* routing, void* workspace,
+                                   size_t ws_bytes, void* stream_main, void* stream_aux) {
+  SCMOE_TRY(check_desc(D, 1, 1));
+  SCMOE_TRY(check_weights(D, W, true));
+  if (D->T == 0) return SCMOE_OK;
+  if (!x_prev || !x_cur || !y || !workspace) return SCMOE_ERR_NULL;
+  if (!view_ok(x_prev, ld_prev, D->d, D->dtype) || !view_ok(x_cur, ld_cur, D->d, D->dtype) ||
+      !view_ok(y, ldy, D->d, D->dtype) || !aligned16(workspace))
+    return SCMOE_ERR_SHAPE;
+  if (residual && !view_ok(residual, ldres, D->d, D->dtype)) return SCMOE_ERR_SHAPE;
+  const LayerWs w = carve(D, workspace, true);
+  if (ws_bytes < w.total) return SCMOE_ERR_WORKSPACE;
+  hipStream_t sm = static_cast<hipStream_t>(stream_main);
+  hipStream_t sa = static_cast<hipStream_t>(stream_aux);
+  const bool two = stream_aux != nullptr && sa != sm;
+  hipStream_t s_shared = two ? sa : sm;
+  EventPair* ev = nullptr;
+  if (two) {
+    SCMOE_TRY(get_events(&ev));
+    hipError_t e = hipEventRecord(ev->fork, sm);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipStreamWaitEvent(sa, ev->fork, 0);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  // shared expert on the current-layer representation (Eq. (6)/(7)): independent of routing
+  hipLaunchKernelGGL(set_pair, dim3(1), dim3(64), 0, s_shared, w.offsets_shared, 0, D->T);
+  SCMOE_TRY(launch_status());
+  SCMOE_TRY(expert_ffn_any(x_cur, ld_cur, D->dtype, nullptr, w.offsets_shared, D->T, 1, D->d, D->F, W->W1s,
+                           W->b1s, W->W2s, W->b2s, w.hidden_s, w.s, D->d, D->gelu_mode, s_shared));
+  if (D->cg_mode != SCMOE_CG_NONE)
+    SCMOE_TRY(coef_gate(x_cur, ld_cur, D->dtype, W->W_cg, D->cg_mode, D->T, D->d, w.coef, s_shared));
+  if (two) {
+    hipError_t e = hipEventRecord(ev->join, sa);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  // routed experts on the preceding-layer representation
+  SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm));
+  if (two) {
+    hipError_t e = hipStreamWaitEvent(sm, ev->join, 0);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  SCMOE_TRY(combine(w.y_perm, D->d, D->dtype, w.dst_row, w.gate_w, D->T, D->d, 1, w.s, D->d, residual, ldres,
+                    D->cg_mode != SCMOE_CG_NONE ? w.coef : nullptr, y, ldy, sm));
+  return copy_routing(D, w, routing, sm);
+}
+
+extern "C" int moe_topk_layer_forward(const scmoe_desc* D, const void* x, int64_t ldx,
+                                      const scmoe_weights* W, void* y, int64_t ldy,
+                                      const scmoe_routing_out* routing, void* workspace,
+                                      size_t ws_bytes, void* stream) {
+  SCMOE_TRY(check_desc(D, 1, 2));
+  SCMOE_TRY(check_weights(D, W, false));
+  if (D->T == 0) return SCMOE_OK;
+  if (!x || !y || !workspace) return SCMOE_ERR_NULL;
+  if (!view_ok(x, ldx, D->d, D->dtype) || !view_ok(y, ldy, D->d, D->dtype) || !aligned16(workspace))
+    return SCMOE_ERR_SHAPE;
+  const LayerWs w = carve(D, workspace, false);
+  if (ws_bytes < w.total) return SCMOE_ERR_WORKSPACE;
+  hipStream_t sm = static_cast<hipStream_t>(stream);
+  SCMOE_TRY(routed_chain(D, x, ldx, W, w, sm));
+  SCMOE_TRY(combine(w.y_perm, D->d, D->dtype, w.dst_row, w.gate_w, D->T, D->d, D->k, nullptr, 0, nullptr, 0,
+                    nullptr, y, ldy, sm));
+  return copy_routing(D, w, routing, sm);
+}
+
+extern "C" int moe_top2_layer_forward(const scmoe_desc* D, const void* x, int64_t ldx,
+                                      const scmoe_weights* W, void* y, int64_t ldy,
+                                      const scmoe_routing_out* routing, void* workspace,
+                                      size_t ws_bytes, void* stream) {
+  if (D && D->k != 2) return SCMOE_ERR_ARG;
+  return moe_topk_layer_forward(D, x, ldx, W, y, ldy, routing, workspace, ws_bytes, stream);
+}

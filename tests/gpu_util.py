@@ -1,0 +1,92 @@
+"""Helpers of the GPU parity tests: numpy layer tensors -> device tensors, error metric."""
+import numpy as np
+import torch
+
+from paper_2404_05019_amd import binding as B
+from paper_2404_05019_amd import inputs
+
+DEV = "cuda:0"
+
+
+def to_dev(a, dtype):
+    """float32 numpy array whose values are representable in `dtype` -> device tensor."""
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == "bf16":
+        bits = inputs.bf16_bits(a)
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(DEV)
+    return torch.from_numpy(a).to(DEV)
+
+
+def to_host(t):
+    return t.detach().float().cpu().numpy()
+
+
+def relerr(g, r):
+    """max |g - r| / max |r|: the error metric of the parity bar."""
+    g = np.asarray(g, np.float64)
+    r = np.asarray(r, np.float64)
+    den = np.abs(r).max()
+    return float(np.abs(g - r).max() / (den if den > 0 else 1.0))
+
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+class DevLayer:
+    """Device copies of a layer dict from inputs.make_layer, plus the weights struct."""
+
+    def __init__(self, L, dtype):
+        self.dtype = dtype
+        act = lambda k: to_dev(L.get(k), dtype)
+        f32 = lambda k: to_dev(L.get(k), "f32")
+        self.x_prev, self.x_cur = act("x_prev"), act("x_cur")
+        self.Wg, self.bias = f32("Wg"), f32("bias")
+        self.W1, self.W2, self.W1s, self.W2s = act("W1"), act("W2"), act("W1s"), act("W2s")
+        self.b1, self.b2, self.b1s, self.b2s = f32("b1"), f32("b2"), f32("b1s"), f32("b2s")
+        self.Wcg = f32("Wcg")
+        self.weights = B.make_weights(self.Wg, self.W1, self.W2, self.W1s, self.W2s, self.bias, self.b1,
+                                      self.b2, self.b1s, self.b2s, self.Wcg)
+        self.E, self.F, self.d = self.W1.shape
+        self.T = self.x_cur.shape[0]
+        self.code = B.BF16 if dtype == "bf16" else B.F32
+        self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def run_layer(D, k=1, capacity=None, shared=True, normalize=0, cg_mode=0, gelu_mode=0, residual=False,
+              two_streams=False):
+    """Call the layer entry point; returns (y numpy float32, routing dict of numpy arrays)."""
+    T, E = D.T, D.E
+    C_ = T * k if capacity is None else capacity
+    desc = B.make_desc(T, D.d, D.F, E, k, C_, D.code, gelu_mode, normalize, cg_mode)
+    ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    y = torch.empty((T, D.d), dtype=D.tdtype, device=DEV)
+    rows = min(T * k, E * C_)
+    r = dict(expert_idx=torch.empty(T * k, dtype=torch.int32, device=DEV),
+             gate_w=torch.empty(T * k, dtype=torch.float32, device=DEV),
+             counts=torch.empty(E, dtype=torch.int32, device=DEV),
+             offsets=torch.empty(E + 1, dtype=torch.int32, device=DEV),
+             dst_row=torch.empty(T * k, dtype=torch.int32, device=DEV),
+             src_token=torch.full((max(rows, 1),), -1, dtype=torch.int32, device=DEV))
+    rout = B.make_routing_out(**r)
+    if shared:
+        aux = torch.cuda.Stream() if two_streams else None
+        B.scmoe_layer_forward(desc, D.x_prev, D.x_cur, D.weights, y, ws,
+                              residual=D.x_cur if residual else None, routing=rout, stream_aux=aux)
+    else:
+        B.moe_topk_layer_forward(desc, D.x_cur, D.weights, y, ws, routing=rout)
+    torch.cuda.synchronize()
+    out = {n: t.cpu().numpy() for n, t in r.items()}
+    Kk = int(out["offsets"][E])
+    routing = dict(idx=out["expert_idx"].reshape(T, k), w=out["gate_w"].reshape(T, k), counts=out["counts"],
+                   offsets=out["offsets"], dst_row=out["dst_row"].reshape(T, k),
+                   src_token=out["src_token"][:Kk])
+    return to_host(y), routing
+
+
+def assert_routing_equal(g, r, w_tol=1e-6):
+    """Integer routing state must match bit for bit; gate weights are floats."""
+    for key in ("idx", "counts", "offsets", "dst_row", "src_token"):
+        assert np.array_equal(g[key], r[key]), "routing array %s differs" % key
+    assert np.abs(g["w"].astype(np.float64) - r["w"].astype(np.float64)).max() <= w_tol

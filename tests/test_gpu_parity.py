@@ -1,0 +1,329 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+
+Bars: routing indices, counts, offsets and the permutation bit-exact; float outputs within
+max|g-r| / max|r| <= 1e-4 (fp32) and 2e-2 (bf16); gate weights within 1e-6.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2404_05019_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2404_05019_amd import binding as B
+    from gpu_util import DEV, TOL, DevLayer, assert_routing_equal, relerr, run_layer, to_dev, to_host
+
+
+def _i32(n, fill=None):
+    if fill is None:
+        return torch.empty(n, dtype=torch.int32, device=DEV)
+    return torch.full((n,), fill, dtype=torch.int32, device=DEV)
+
+
+# ------------------------------------------------------------------------------------- gate
+
+@pytest.mark.parametrize("T,d,E,dtype,k,use_bias", [
+    (256, 64, 4, "f32", 1, False), (1000, 384, 8, "bf16", 1, False), (777, 1024, 16, "bf16", 1, True),
+    (130, 72, 3, "f32", 2, True), (513, 264, 64, "bf16", 2, False), (64, 8, 1, "bf16", 1, False),
+    (4099, 2048, 16, "bf16", 2, True), (300, 128, 33, "f32", 1, True), (1, 16, 2, "f32", 2, False)])
+@pytest.mark.parametrize("normalize", [0, 1])
+def test_gate_parity(oracle, T, d, E, dtype, k, use_bias, normalize):
+    rng = np.random.default_rng(T + d + E)
+    x = inputs.quantize(rng.standard_normal((T, d)), dtype)
+    Wg = (0.02 * rng.standard_normal((d, E))).astype(np.float32)
+    bias = (0.3 * rng.standard_normal(E)).astype(np.float32) if use_bias else None
+    idx, w, probs = oracle.gate(x, Wg, bias, k, normalize)
+    gx, gW, gb = to_dev(x, dtype), to_dev(Wg, "f32"), to_dev(bias, "f32")
+    gi, gw = _i32(T * k), torch.empty(T * k, dtype=torch.float32, device=DEV)
+    gp = torch.empty((T, E), dtype=torch.float32, device=DEV)
+    fn = B.scmoe_gate_top1 if k == 1 else B.scmoe_gate_top2
+    fn(gx, gW, gb, gi, gw, gp, normalize=normalize)
+    torch.cuda.synchronize()
+    assert np.array_equal(gi.cpu().numpy().reshape(T, k), idx)
+    assert np.abs(gw.cpu().numpy().reshape(T, k).astype(np.float64) - w).max() <= 1e-6
+    assert np.abs(gp.cpu().numpy().astype(np.float64) - probs).max() <= 1e-6
+
+
+def test_gate_integer_ties_and_strided_view(oracle):
+    """Integer inputs: logits exact, many ties, lowest index must win on both sides; x is
+    passed as a strided view (ldx > d)."""
+    rng = np.random.default_rng(5)
+    T, d, E = 700, 16, 6
+    x = rng.integers(-2, 3, (T, d)).astype(np.float32)
+    Wg = rng.integers(-1, 2, (d, E)).astype(np.float32)
+    idx, w, _ = oracle.gate(x, Wg, None, 2, 1)
+    big = torch.zeros((T, d + 24), dtype=torch.float32, device=DEV)
+    big[:, :d] = torch.from_numpy(x).to(DEV)
+    gi, gw = _i32(T * 2), torch.empty(T * 2, dtype=torch.float32, device=DEV)
+    B.scmoe_gate_top2(big[:, :d], to_dev(Wg, "f32"), None, gi, gw, None, normalize=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(gi.cpu().numpy().reshape(T, 2), idx)
+
+
+def test_gate_nan_rule(oracle):
+    """A NaN logit never wins over a number (NaN arrives through the bias)."""
+    T, d, E = 64, 8, 4
+    x = np.ones((T, d), np.float32)
+    Wg = np.tile(np.array([0.1, 0.2, 0.3, 0.25], np.float32), (d, 1))
+    bias = np.array([0.0, 0.0, np.nan, 0.0], np.float32)
+    idx, _, _ = oracle.gate(x, Wg, bias, 2, 1)
+    gi, gw = _i32(T * 2), torch.empty(T * 2, dtype=torch.float32, device=DEV)
+    B.scmoe_gate_top2(to_dev(x, "f32"), to_dev(Wg, "f32"), to_dev(bias, "f32"), gi, gw, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(gi.cpu().numpy().reshape(T, 2), idx)
+    assert idx[0].tolist() == [3, 1]
+
+
+# --------------------------------------------------------------------------------- dispatch
+
+def _run_dispatch(x, idx, E, k, C_, dtype, copy=True):
+    T, d = x.shape
+    gx = to_dev(x, dtype)
+    gi = torch.from_numpy(np.ascontiguousarray(idx, np.int32).reshape(-1)).to(DEV)
+    rows = max(min(T * k, E * C_), 1)
+    counts, offsets, dst_row = _i32(E), _i32(E + 1), _i32(max(T * k, 1))
+    src_token = _i32(rows, -7)
+    x_perm = torch.zeros((rows, d), dtype=gx.dtype, device=DEV) if copy else None
+    ws = torch.empty(max(B.scmoe_dispatch_workspace_bytes(T, E, k), 16), dtype=torch.uint8, device=DEV)
+    B.scmoe_dispatch(gx, gi, E, k, C_, counts, offsets, dst_row, src_token, x_perm, ws)
+    torch.cuda.synchronize()
+    return (counts.cpu().numpy(), offsets.cpu().numpy(), dst_row.cpu().numpy()[:T * k].reshape(T, k),
+            src_token.cpu().numpy(), None if x_perm is None else to_host(x_perm))
+
+
+@pytest.mark.parametrize("T,E,k,C_,d,dtype", [
+    (1, 1, 1, 1, 8, "f32"), (63, 4, 1, 10, 16, "bf16"), (64, 4, 1, 0, 8, "f32"), (257, 4, 1, 257, 24, "bf16"),
+    (5000, 8, 1, 700, 64, "bf16"), (5000, 16, 2, 500, 40, "f32"), (1025, 64, 2, 40, 8, "bf16"),
+    (4096, 7, 2, 100000, 8, "f32"), (300, 1, 1, 17, 8, "bf16")])
+def test_dispatch_parity(oracle, T, E, k, C_, d, dtype):
+    rng = np.random.default_rng(T * 7 + E)
+    x = inputs.quantize(rng.standard_normal((T, d)), dtype)
+    if k == 1:
+        idx = rng.integers(0, E, (T, 1)).astype(np.int32)
+    else:
+        a = rng.integers(0, E, T)
+        b = (a + 1 + rng.integers(0, E - 1, T)) % E
+        idx = np.stack([a, b], 1).astype(np.int32)
+    counts, offsets, dst_row, src_token = oracle.dispatch(idx, E, C_)
+    gc, go, gd, gs, gxp = _run_dispatch(x, idx, E, k, C_, dtype)
+    K = int(offsets[E])
+    assert np.array_equal(gc, counts) and np.array_equal(go, offsets)
+    assert np.array_equal(gd, dst_row)
+    assert np.array_equal(gs[:K], src_token)
+    assert (gs[K:] == -7).all()                       # entries past K are left untouched
+    assert np.array_equal(gxp[:K], x[src_token])      # raw row copy, bit for bit
+    assert (gxp[K:] == 0).all()
+
+
+def test_dispatch_all_to_one_and_invalid(oracle):
+    T, E, C_ = 1000, 5, 300
+    x = np.zeros((T, 8), np.float32)
+    idx = np.full((T, 1), 3, np.int32)
+    idx[5, 0] = -1          # out-of-range entries are dropped, not faults
+    idx[6, 0] = E
+    counts, offsets, dst_row, src_token = oracle.dispatch(idx, E, C_)
+    gc, go, gd, gs, _ = _run_dispatch(x, idx, E, 1, C_, "f32", copy=False)
+    assert np.array_equal(gc, counts) and np.array_equal(go, offsets) and np.array_equal(gd, dst_row)
+    assert gc.tolist() == [0, 0, 0, 300, 0] and gd[5, 0] == -1 and gd[6, 0] == -1
+    assert np.array_equal(gs[:300], src_token)
+
+
+# ------------------------------------------------------------------------------- expert FFN
+
+def _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode, extra_rows=5, w_scale=0.05):
+    rng = np.random.default_rng(E * 100 + d + F)
+    K = int(sum(lens))
+    rows = K + extra_rows
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    x = inputs.quantize(rng.standard_normal((rows, d)), dtype)
+    W1 = inputs.quantize(w_scale * rng.standard_normal((E, F, d)), dtype)
+    W2 = inputs.quantize(w_scale * rng.standard_normal((E, d, F)), dtype)
+    b1 = (0.1 * rng.standard_normal((E, F))).astype(np.float32) if biases else None
+    b2 = (0.1 * rng.standard_normal((E, d))).astype(np.float32) if biases else None
+    ref = oracle.expert_ffn(x, offsets, W1, W2, b1, b2, gelu_mode=gelu_mode)
+    gx = to_dev(x, dtype)
+    hidden = torch.zeros((rows, F), dtype=gx.dtype, device=DEV)
+    y = torch.full((rows, d), 7.0, dtype=gx.dtype, device=DEV)
+    B.scmoe_expert_ffn(gx, torch.from_numpy(offsets).to(DEV), rows, to_dev(W1, dtype), to_dev(b1, "f32"),
+                       to_dev(W2, dtype), to_dev(b2, "f32"), hidden, y, gelu_mode=gelu_mode)
+    torch.cuda.synchronize()
+    g = to_host(y)
+    assert (g[K:] == 7.0).all()                       # rows past offsets[E] are not touched
+    if K:
+        assert relerr(g[:K], ref[:K]) <= TOL[dtype]
+    return g, ref
+
+
+@pytest.mark.parametrize("E,lens,d,F,dtype,biases,gelu_mode", [
+    (4, [64, 60, 70, 62], 64, 256, "f32", False, 0),        # the tiny configuration's shape
+    (3, [5, 0, 130], 24, 40, "f32", True, 1),
+    (2, [33, 31], 72, 40, "bf16", True, 0),                 # bf16 shape outside the MFMA path
+    (1, [300], 64, 64, "bf16", False, 0),
+    (3, [300, 0, 517], 128, 320, "bf16", True, 0),          # several tiles, ragged tails, N tail
+    (4, [256, 1, 255, 257], 192, 448, "bf16", True, 1),
+    (2, [700, 90], 384, 1536, "bf16", False, 0),            # SwinV2-MoE-S stage-3 widths
+    (5, [0, 0, 40, 0, 9], 64, 128, "bf16", True, 0)])
+def test_expert_ffn_parity(oracle, E, lens, d, F, dtype, biases, gelu_mode):
+    _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_expert_ffn_tile_variants(oracle, variant):
+    """Every tile configuration of the MFMA grouped GEMM meets the same bar."""
+    B.scmoe_set_gemm_variant(variant)
+    try:
+        _ffn_case(oracle, 3, [300, 77, 517], 256, 384, "bf16", True, 0)
+        _ffn_case(oracle, 1, [1000], 128, 512, "bf16", False, 0)
+    finally:
+        B.scmoe_set_gemm_variant(0)
+
+
+# --------------------------------------------------------------------------- combine / CG
+
+@pytest.mark.parametrize("T,d,k,dtype,use_base,use_res,use_coef", [
+    (300, 64, 1, "f32", True, False, False), (257, 384, 1, "bf16", True, True, True),
+    (100, 8, 2, "f32", False, False, False), (1000, 1024, 2, "bf16", True, False, True),
+    (64, 2048, 1, "bf16", False, True, False)])
+def test_combine_parity(oracle, T, d, k, dtype, use_base, use_res, use_coef):
+    rng = np.random.default_rng(T + d)
+    K = T * k // 2 + 1
+    yp = inputs.quantize(rng.standard_normal((K, d)), dtype)
+    slots = rng.permutation(T * k)
+    dst = -np.ones(T * k, np.int32)
+    dst[slots[:K]] = rng.permutation(K).astype(np.int32)
+    dst = dst.reshape(T, k)
+    w = rng.random((T, k)).astype(np.float32)
+    base = inputs.quantize(rng.standard_normal((T, d)), dtype) if use_base else None
+    res = inputs.quantize(rng.standard_normal((T, d)), dtype) if use_res else None
+    coef = rng.random((T, 2)).astype(np.float32) if use_coef else None
+    ref = oracle.combine(yp, dst, w, base, res, coef)
+    y = torch.empty((T, d), dtype=to_dev(yp, dtype).dtype, device=DEV)
+    B.scmoe_combine(to_dev(yp, dtype), torch.from_numpy(dst.reshape(-1)).to(DEV), to_dev(w.reshape(-1), "f32"),
+                    k, to_dev(base, dtype), to_dev(res, dtype), to_dev(coef, "f32"), y)
+    torch.cuda.synchronize()
+    assert relerr(to_host(y), ref) <= (1e-6 if dtype == "f32" else 4e-3)
+
+
+@pytest.mark.parametrize("mode,dtype,d", [(1, "f32", 64), (2, "bf16", 384), (1, "bf16", 2048), (2, "f32", 72)])
+def test_coef_gate_parity(oracle, mode, dtype, d):
+    rng = np.random.default_rng(d + mode)
+    T = 333
+    x = inputs.quantize(rng.standard_normal((T, d)), dtype)
+    Wcg = (0.05 * rng.standard_normal((mode, d))).astype(np.float32)
+    ref = oracle.coef_gate(x, Wcg, mode)
+    coef = torch.empty((T, 2), dtype=torch.float32, device=DEV)
+    B.scmoe_coef_gate(to_dev(x, dtype), to_dev(Wcg, "f32"), mode, coef)
+    torch.cuda.synchronize()
+    assert np.abs(coef.cpu().numpy() - ref).max() <= 1e-5
+
+
+# -------------------------------------------------------------------------------- the layer
+
+def _layer_case(oracle, L, dtype, E, k, C_, shared, normalize=0, cg_mode=0, gelu_mode=0, residual=False,
+                two_streams=False):
+    D = DevLayer(L, dtype)
+    y, r = run_layer(D, k, C_, shared, normalize, cg_mode, gelu_mode, residual, two_streams)
+    ref, rr = oracle.layer_forward(L["x_prev"], L["x_cur"], L, k=k, capacity_=C_, shared=int(shared),
+                                   normalize=normalize, cg_mode=cg_mode, gelu_mode=gelu_mode,
+                                   add_residual=int(residual))
+    assert_routing_equal(r, rr)
+    assert relerr(y, ref) <= TOL[dtype]
+    return y, r, ref, rr
+
+
+@pytest.mark.parametrize("two_streams", [False, True])
+def test_layer_tiny_config(oracle, two_streams):
+    """BASELINE configuration 1: T=256, d=64, F=256, E=4, fp32, cf 1.25 (C=80)."""
+    L, cfg = inputs.make_config("tiny")
+    y, r, ref, rr = _layer_case(oracle, L, "f32", cfg["E"], 1, cfg["C"], True, two_streams=two_streams)
+    assert cfg["C"] == 80 and int(r["offsets"][-1]) == int((r["dst_row"] >= 0).sum())
+
+
+@pytest.mark.parametrize("k,shared,C_,normalize,cg,res,gelu", [
+    (1, True, 200, 0, 0, False, 0), (1, True, 100000, 0, 1, True, 0), (1, True, 150, 0, 2, False, 1),
+    (2, False, 300, 1, 0, False, 0), (2, False, 100000, 0, 0, False, 0), (1, False, 0, 0, 0, False, 0),
+    (1, True, 0, 1, 0, False, 0)])
+def test_layer_bf16_mfma_path(oracle, k, shared, C_, normalize, cg, res, gelu):
+    """bf16 layer on the MFMA path with gather-on-load: ragged T, binding capacity, drops."""
+    L = inputs.make_layer(T=700, d=128, F=256, E=4, dtype="bf16", seed=11 + k, biases=True, cg_rows=cg,
+                          w_scale=0.05)
+    y, r, ref, rr = _layer_case(oracle, L, "bf16", 4, k, C_, shared, normalize, cg, gelu, res, two_streams=shared)
+    if shared and cg == 0 and not res:
+        # dropped tokens: the expert term is exactly zero, so y equals the shared output
+        dropped = r["dst_row"][:, 0] < 0
+        D = DevLayer(dict(L, W2=np.zeros_like(L["W2"]), b2=np.zeros_like(L["b2"])), "bf16")
+        s, _ = run_layer(D, 1, C_, True, normalize)
+        assert np.array_equal(y[dropped], s[dropped])
+
+
+def test_layer_f32_generic_path_with_options(oracle):
+    L = inputs.make_layer(T=333, d=40, F=72, E=5, dtype="f32", seed=21, biases=True, cg_rows=1, w_scale=0.1)
+    _layer_case(oracle, L, "f32", 5, 1, 50, True, cg_mode=1, residual=True)
+    _layer_case(oracle, L, "f32", 5, 2, 90, False, normalize=1)
+
+
+def test_shared_expert_moe_is_scmoe_with_equal_inputs(oracle):
+    """Eq. (6) is Eq. (7) with x_prev == x_cur."""
+    L = inputs.make_layer(T=500, d=64, F=128, E=4, dtype="bf16", seed=31, w_scale=0.05)
+    L["x_prev"] = L["x_cur"]
+    _layer_case(oracle, L, "bf16", 4, 1, 200, True)
+
+
+def test_layer_is_deterministic(oracle):
+    L = inputs.make_layer(T=3000, d=128, F=256, E=8, dtype="bf16", seed=41, w_scale=0.05)
+    D = DevLayer(L, "bf16")
+    outs = [run_layer(D, 1, 300, True, two_streams=(i % 2 == 1)) for i in range(3)]
+    for y, r in outs[1:]:
+        assert np.array_equal(y, outs[0][0])
+        for key in ("idx", "counts", "offsets", "dst_row", "src_token", "w"):
+            assert np.array_equal(r[key], outs[0][1][key])
+
+
+# --------------------------------------------------- full benchmark sizes, sampled rows
+
+def _full_size(oracle, name, n_sample, k=1, shared=True, normalize=0):
+    """Routing compared for every token; output rows compared on a seeded sample (the
+    oracle evaluates those tokens one by one)."""
+    L, cfg = inputs.make_config(name)
+    T, E = cfg["T"], cfg["E"]
+    C_ = inputs.capacity(T, E, k, cfg["cf"])
+    D = DevLayer(L, cfg["dtype"])
+    y, r = run_layer(D, k, C_, shared, normalize, two_streams=shared)
+    xg = L["x_prev"] if shared else L["x_cur"]
+    rr = oracle.route(xg, L, E, k, C_, normalize)
+    assert_routing_equal(r, rr)
+    assert (r["counts"] <= C_).all() and r["counts"].sum() == (r["dst_row"] >= 0).sum()
+    rng = np.random.default_rng(1234)
+    dropped = np.nonzero((rr["dst_row"] < 0).any(axis=1))[0]
+    tokens = np.unique(np.concatenate([rng.integers(0, T, n_sample), [0, T - 1], dropped[:8]])).astype(np.int32)
+    ref = oracle.layer_rows(L["x_prev"], L["x_cur"], L, rr, tokens, k=k, shared=int(shared))
+    err = relerr(y[tokens], ref)
+    assert err <= TOL[cfg["dtype"]], err
+    return cfg, r
+
+
+def test_full_size_small(oracle):
+    cfg, r = _full_size(oracle, "small", 256)
+    assert cfg["C"] == 1280 and int(r["offsets"][-1]) == cfg["T"]      # near-uniform: no drops
+
+
+def test_full_size_medium_and_top2_baseline(oracle):
+    cfg, r = _full_size(oracle, "medium", 96)
+    assert cfg["C"] == 2560
+    cfg2, r2 = _full_size(oracle, "medium", 64, k=2, shared=False, normalize=1)
+    assert int(r2["offsets"][-1]) <= 2 * cfg["T"]
+
+
+def test_full_size_skewed(oracle):
+    """Zipf(1.2) expert load with capacity factor 1.0: a large share of tokens is dropped."""
+    cfg, r = _full_size(oracle, "skewed", 96)
+    kept = int(r["offsets"][-1])
+    assert cfg["C"] == 1024 and 0.4 * cfg["T"] < kept < 0.75 * cfg["T"]
+    assert (r["counts"][:3] == 1024).all()
+
+
+def test_full_size_large(oracle):
+    cfg, r = _full_size(oracle, "large", 48)
+    assert cfg["C"] == 2560
