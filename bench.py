@@ -1,0 +1,185 @@
+"""Benchmark of one ScMoE block forward on one MI355X.
+
+A step is one pass of the whole hot path (gate -> dispatch -> routed experts, shared expert,
+combine) through scmoe_layer_forward over one batch of seeded synthetic input that is
+already resident in HBM.  Prints ONE JSON line: layer tokens/s, the roofline record of the
+dominant kernel (the bf16 MFMA grouped GEMM), per-operator HBM rates, and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="large", help="tiny|small|medium|skewed|large")
+    ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
+                    help="1: all kernels in order on one stream; 2: shared expert on a second stream")
+    ap.add_argument("--gemm-variant", type=int, default=None)
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def time_region(torch, fn, steps, warmup):
+    """Average milliseconds of fn() over `steps` calls, HIP events on the current stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2404_05019_amd import binding as B
+    from paper_2404_05019_amd import inputs
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import DEV, DevLayer
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.gemm_variant is not None:
+        B.scmoe_set_gemm_variant(args.gemm_variant)
+
+    t_gen = time.time()
+    L, cfg = inputs.make_config(args.workload)
+    T, d, F, E, C_ = cfg["T"], cfg["d"], cfg["F"], cfg["E"], cfg["C"]
+    dtype = cfg["dtype"]
+    eb = 2 if dtype == "bf16" else 4
+    D = DevLayer(L, dtype)
+    t_gen = time.time() - t_gen
+
+    desc = B.make_desc(T, d, F, E, 1, C_, D.code)
+    ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    y = torch.empty((T, d), dtype=D.tdtype, device=DEV)
+    aux = torch.cuda.Stream() if args.streams == 2 else None
+
+    def step():
+        B.scmoe_layer_forward(desc, D.x_prev, D.x_cur, D.weights, y, ws, stream_aux=aux)
+
+    # ---- the timed region: exactly `steps` layer forwards between two synchronisations ----
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    tokens_per_s = T / (ms_per_step * 1e-3)
+
+    # ---- per-operator legs through the same C entry points, on the current stream --------
+    i32 = lambda n: torch.empty(max(n, 1), dtype=torch.int32, device=DEV)
+    idx, gw = i32(T), torch.empty(T, dtype=torch.float32, device=DEV)
+    counts, offsets, dst_row, src_token = i32(E), i32(E + 1), i32(T), i32(min(T, E * C_))
+    rows = min(T, E * C_)
+    x_perm = torch.empty((rows, d), dtype=D.tdtype, device=DEV)
+    hidden = torch.empty((rows, F), dtype=D.tdtype, device=DEV)
+    y_perm = torch.empty((rows, d), dtype=D.tdtype, device=DEV)
+    s_out = torch.empty((T, d), dtype=D.tdtype, device=DEV)
+    dws = torch.empty(max(B.scmoe_dispatch_workspace_bytes(T, E, 1), 16), dtype=torch.uint8, device=DEV)
+    B.scmoe_gate_top1(D.x_prev, D.Wg, D.bias, idx, gw)
+    B.scmoe_dispatch(D.x_prev, idx, E, 1, C_, counts, offsets, dst_row, src_token, x_perm, dws)
+    torch.cuda.synchronize()
+    K = int(offsets[E].item())
+    n_ops = max(args.steps, 10)
+    ms_gate = time_region(torch, lambda: B.scmoe_gate_top1(D.x_prev, D.Wg, D.bias, idx, gw), n_ops, 3)
+    ms_disp = time_region(torch, lambda: B.scmoe_dispatch(D.x_prev, idx, E, 1, C_, counts, offsets, dst_row,
+                                                          src_token, x_perm, dws), n_ops, 3)
+    ms_ffn = time_region(torch, lambda: B.scmoe_expert_ffn(x_perm, offsets, rows, D.W1, D.b1, D.W2, D.b2, hidden,
+                                                           y_perm), args.steps, 2)
+    ms_comb = time_region(torch, lambda: B.scmoe_combine(y_perm, dst_row, gw, 1, s_out, None, None, y), n_ops, 3)
+
+    # algorithmic work per unit (kept row / token) of each operator
+    ffn_flops = 4.0 * K * d * F                       # two GEMMs of 2*K*d*F each
+    gate_bytes = T * (d * eb + 8)
+    disp_bytes = K * (2 * d * eb + 12)
+    comb_bytes = T * (2 * d * eb + 8) + K * d * eb
+    is_mfma = dtype == "bf16"
+    ach_tflops = ffn_flops / (ms_ffn * 1e-3) / 1e12
+    roofline = {
+        "kernel": "gemm_bf16_kernel (grouped GEMM of scmoe_expert_ffn; 2 launches per call)",
+        "bound": "mfma" if is_mfma else "alu",
+        "achieved": round(ach_tflops, 2),
+        "peak": PEAK_BF16_TFLOPS if is_mfma else 78.6,
+        "unit": "TFLOP/s",
+        "frac": round(ach_tflops / (PEAK_BF16_TFLOPS if is_mfma else 78.6), 4),
+        "traffic": None,
+        "flops_per_launch": ffn_flops / 2,
+        "avg_launch_ms": round(ms_ffn / 2, 4),
+        "launches_per_call": 2,
+    }
+    gbs = lambda b, ms: round(b / (ms * 1e-3) / 1e9, 1)
+    ops = {
+        "gate": {"ms": round(ms_gate, 4), "GB/s": gbs(gate_bytes, ms_gate), "frac_hbm": round(gbs(gate_bytes, ms_gate) / PEAK_HBM_GBS, 4)},
+        "dispatch": {"ms": round(ms_disp, 4), "GB/s": gbs(disp_bytes, ms_disp), "frac_hbm": round(gbs(disp_bytes, ms_disp) / PEAK_HBM_GBS, 4)},
+        "expert_ffn": {"ms": round(ms_ffn, 4), "TFLOP/s": round(ach_tflops, 2)},
+        "combine": {"ms": round(ms_comb, 4), "GB/s": gbs(comb_bytes, ms_comb), "frac_hbm": round(gbs(comb_bytes, ms_comb) / PEAK_HBM_GBS, 4)},
+    }
+
+    # ---- CPU oracle on a bounded sample of the same workload ------------------------------
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import cpu as oracle
+        t0 = time.perf_counter()
+        rr = oracle.route(L["x_prev"], L, E, 1, C_)
+        t_route = time.perf_counter() - t0
+        rng = np.random.default_rng(99)
+        probe = rng.integers(0, T, 2 * oracle.num_threads()).astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.layer_rows(L["x_prev"], L["x_cur"], L, rr, probe, k=1, shared=1)
+        per_tok = (time.perf_counter() - t0) / len(probe)
+        n = int(min(T, max(len(probe), args.cpu_seconds / max(per_tok, 1e-9))))
+        n -= n % oracle.num_threads() if n > oracle.num_threads() else 0
+        sample = rng.integers(0, T, n).astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.layer_rows(L["x_prev"], L["x_cur"], L, rr, sample, k=1, shared=1)
+        t_rows = time.perf_counter() - t0
+        est_total = t_route + t_rows * (T / n)
+        cpu_baseline = {
+            "value": round(T / est_total, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "gate+dispatch of all %d tokens (%.2f s) + Eq.(7) rows of %d sampled tokens (%.2f s), "
+                      "scaled to T tokens" % (T, t_route, n, t_rows),
+        }
+
+    out = {
+        "metric": "ScMoE layer forward tokens/s (1 MI355X)", "value": round(tokens_per_s, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if is_mfma else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "T": T, "d_model": d, "d_ffn": F, "E": E, "top_k": 1,
+                   "capacity": C_, "kept_rows": K, "streams": args.streams},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "ops": ops,
+        "layer_tflops": round((4.0 * (K + T) * d * F) / (ms_per_step * 1e-3) / 1e12, 2),
+        "input_generation_s": round(t_gen, 1),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
