@@ -13,8 +13,9 @@
 //    lane, no VGPR staging).  Such a load writes 1 KiB of consecutive LDS per wave, so the
 //    bank-conflict swizzle is applied on the global side: the lane that fills LDS slot
 //    (row, c) fetches k-chunk  c ^ swz(row)  of that row.
-//  * LDS is double buffered: the loads of k-tile t+1 are in flight while the waves issue
-//    the MFMAs of k-tile t; one workgroup barrier per k-tile.
+//  * LDS is double buffered and the register fragments are double buffered too: global
+//    loads run one k-tile ahead, LDS reads one k16-step ahead of the MFMAs; one workgroup
+//    barrier per k-tile.
 //  * The MFMA is issued with the weight fragment as its first operand, so a lane ends up
 //    holding 4 consecutive output columns of one row and stores them as one 8-byte piece.
 //  * Workgroup ids are remapped so that each XCD (ids congruent mod 8 land on one XCD and
@@ -35,26 +36,31 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 #define SCMOE_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define SCMOE_GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-// XOR swizzles of the 16-byte chunk index inside an LDS row.  Chosen so that 8 or 16
-// consecutive rows reading the same logical chunk fall into distinct bank groups.
+// XOR swizzle of the 16-byte chunk index inside an LDS row.  A 64-lane ds_read_b128 is
+// served in four passes of 16 lanes, and on gfx950 the passes are NOT runs of consecutive
+// lanes (measured with a pairwise timing probe): {0-3, 12-15, 20-27}, {4-11, 16-19, 28-31}
+// and the same two sets + 32.  A fragment read has lane l on row l % 32, so one pass covers
+// the rows listed above with one logical chunk; the 16 accesses must fall into 16 distinct
+// 16-byte bank groups of the 256-byte bank window.  With 128-byte rows (two rows per window)
+// chunk ^ (row/2 % 8) does that, with 64-byte rows (four per window) chunk ^ (row/4 % 4).
 template <int CPR>
 __host__ __device__ constexpr int swz(int r) {
-  return CPR == 8 ? ((r + (r >> 3)) & 7) : (((r >> 1) + (r >> 3)) & 3);
+  return CPR == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3);
 }
+
 
 struct GemmArgs {
   const unsigned char* A;   // activations, bf16 [rows, Kd]
   int64_t lda;              // row stride of A in elements
   const int32_t* gather;    // row r of the packed order reads A[gather[r]]; nullptr = identity
   const int32_t* offsets;   // [E + 1] segment starts, device
-  const unsigned char* W;   // bf16 [E, N, Kd]
+  const unsigned char* W;   // bf16 [E, N, Kd], row stride ldw
+  int64_t ldw;              // row stride of W in elements (>= Kd)
   const float* bias;        // [E, N] or nullptr
   unsigned char* C;         // bf16 [rows, N], row stride ldc
   int64_t ldc;
   int E, N, Kd;
-  int mtb;                  // upper bound on row tiles, multiple of the raster group
   int nt;                   // column tiles
-  int chunk;                // logical tiles per XCD
   int gelu_mode;
 };
 
@@ -90,9 +96,9 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_>
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_>
 struct TileCfg {
-  static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_;   // NS: LDS stages
   static constexpr int WAVES = WM * WN, THREADS = 64 * WAVES;
   static constexpr int TM = BM / WM, TN = BN / WN;       // wave tile
   static constexpr int MI = TM / 32, NJ = TN / 32;       // 32x32 MFMA tiles per wave
@@ -101,10 +107,12 @@ struct TileCfg {
   static constexpr int RPL = 64 / CPR;                   // rows filled by one wave-wide load
   static constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB, STAGE = A_BYTES + B_BYTES;
   static constexpr int A_PER_WAVE = BM / RPL / WAVES, B_PER_WAVE = BN / RPL / WAVES;
-  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int LDS_BYTES = NS * STAGE;
+  // workgroups of this shape that fit one CU (512 VGPRs per SIMD lane, 160 KiB LDS)
+  static constexpr int WG_PER_CU = (160 * 1024 / LDS_BYTES) < (8 / WAVES) ? (160 * 1024 / LDS_BYTES) : (8 / WAVES);
   static constexpr int GM = 4;                           // row tiles per raster group
   static_assert(BM % (RPL * WAVES) == 0 && BN % (RPL * WAVES) == 0, "loads must divide evenly");
-  static_assert(TM % 32 == 0 && TN % 32 == 0 && (BK == 32 || BK == 64), "tile shape");
+  static_assert(TM % 32 == 0 && TN % 32 == 0 && (BK == 32 || BK == 64) && NS >= 2 && NS <= 4, "tile shape");
 };
 
 template <class CFG, bool ACT>
@@ -118,15 +126,23 @@ __global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmAr
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // ---- which tile? ----------------------------------------------------------------------
+  // Row tiles are counted from offsets[] here, so that the eight XCDs get equal shares of
+  // the tiles that really exist (the grid is sized for an upper bound).  Workgroup ids
+  // congruent mod 8 run on one XCD; each XCD walks a contiguous range of the raster order
+  // "GM row tiles x all column tiles", which keeps its L2 working set compact.
+  int mt_total = 0;
+  for (int q = 0; q < p.E; ++q) mt_total += (p.offsets[q + 1] - p.offsets[q] + BM - 1) / BM;
+  const int total = mt_total * p.nt;
+  const int chunk = (total + 7) >> 3;
   const int bid = blockIdx.x;
-  const int L = (bid & 7) * p.chunk + (bid >> 3);
-  if (L >= p.mtb * p.nt) return;
+  const int L = (bid & 7) * chunk + (bid >> 3);
+  if ((bid >> 3) >= chunk || L >= total) return;
   const int grp = L / (CFG::GM * p.nt);
   const int rem = L - grp * CFG::GM * p.nt;
-  int mt = grp * CFG::GM + rem % CFG::GM;
-  const int n0 = (rem / CFG::GM) * BN;
+  const int grows = (mt_total - grp * CFG::GM < CFG::GM) ? mt_total - grp * CFG::GM : CFG::GM;
+  int mt = grp * CFG::GM + rem % grows;
+  const int n0 = (rem / grows) * BN;
   int e = 0, row0 = 0, row_end = 0;
-  bool found = false;
   for (e = 0; e < p.E; ++e) {
     const int s = p.offsets[e];
     const int c = p.offsets[e + 1] - s;
@@ -134,15 +150,14 @@ __global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmAr
     if (mt < ntile) {
       row0 = s + mt * BM;
       row_end = s + c;
-      found = true;
       break;
     }
     mt -= ntile;
   }
-  if (!found) return;
+  if (e == p.E) return;   // not reachable: mt < mt_total
 
   // ---- per-lane source addresses of the direct-to-LDS loads -------------------------------
-  const unsigned char* We = p.W + static_cast<int64_t>(e) * p.N * p.Kd * 2;
+  const unsigned char* We = p.W + static_cast<int64_t>(e) * p.N * p.ldw * 2;
   const unsigned char* aptr[CFG::A_PER_WAVE];
   const unsigned char* bptr[CFG::B_PER_WAVE];
 #pragma unroll
@@ -160,7 +175,7 @@ __global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmAr
     const int kc = (lane % CPR) ^ swz<CPR>(row);
     int n = n0 + row;
     if (n > p.N - 1) n = p.N - 1;
-    bptr[i] = We + static_cast<int64_t>(n) * p.Kd * 2 + kc * 16;
+    bptr[i] = We + static_cast<int64_t>(n) * p.ldw * 2 + kc * 16;
   }
 
   auto issue_loads = [&](int kt, int stage) {
@@ -199,32 +214,71 @@ __global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmAr
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  const int nk = p.Kd / BK;
-  issue_loads(0, 0);
-  for (int kt = 0; kt < nk; ++kt) {
-    const int stage = kt & 1;
-    // this wave's loads of k-tile kt have landed; after the barrier everybody's have, and
-    // nobody still reads the other stage (it was consumed in iteration kt-1)
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < nk) issue_loads(kt + 1, stage ^ 1);
-    const unsigned char* st = smem + stage * STAGE;
+  // Software pipeline.  Global -> LDS: two k-tiles in flight (one per LDS stage).  LDS ->
+  // registers: the fragments of k16-step s+1 are fetched while the MFMAs of step s issue,
+  // and the first fragments of the next k-tile are fetched (after the one barrier per
+  // k-tile) under the MFMAs of the last step, so no MFMA waits on an LDS round trip.
+  constexpr int KS = BK / 16;                                   // k16-steps per k-tile (even)
+  constexpr int LPW = CFG::A_PER_WAVE + CFG::B_PER_WAVE;        // direct loads per wave and k-tile
+  bf16x8_t xf[2][MI], wf[2][NJ];
+  auto load_frags = [&](const unsigned char* st, int s, int buf) {
 #pragma unroll
-    for (int s = 0; s < BK / 16; ++s) {
-      // k16-step s reads chunks 2s and 2s+1: XOR on the swizzled chunk index
-      bf16x8_t xf[MI], wf[NJ];
+    for (int i = 0; i < MI; ++i)
+      xf[buf][i] = *reinterpret_cast<const bf16x8_t*>(st + (xoff[i] ^ (s << 5)));
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-        xf[i] = *reinterpret_cast<const bf16x8_t*>(st + (xoff[i] ^ (s << 5)));
+    for (int j = 0; j < NJ; ++j)
+      wf[buf][j] = *reinterpret_cast<const bf16x8_t*>(st + (woff[j] ^ (s << 5)));
+  };
+  auto mfma_step = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
-        wf[j] = *reinterpret_cast<const bf16x8_t*>(st + (woff[j] ^ (s << 5)));
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[i][j], 0, 0, 0);
+  };
+
+  const int nk = p.Kd / BK;
+  constexpr int NS = CFG::NS;
+  // wait until at most `tiles` of the newest k-tiles are still in flight (loads complete in
+  // issue order, LPW loads per k-tile and wave)
+  auto wait_tiles = [&](int tiles) {
+    if (tiles >= 2) __builtin_amdgcn_s_waitcnt(((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14) | 0x0F70);
+    else if (tiles == 1) __builtin_amdgcn_s_waitcnt((LPW & 15) | ((LPW >> 4) << 14) | 0x0F70);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+  };
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
+  for (int t = 0; t < NS; ++t)
+    if (t < nk) issue_loads(t, t);
+  wait_tiles((nk < NS ? nk : NS) - 1);
+  __syncthreads();
+  load_frags(smem, 0, 0);
+  int stage = 0;                      // kt % NS
+  for (int kt = 0; kt < nk; ++kt) {
+    const unsigned char* st = smem + stage * STAGE;
+    const int next = (stage + 1 == NS) ? 0 : stage + 1;
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], xf[i], acc[i][j], 0, 0, 0);
+    for (int s = 0; s + 1 < KS; ++s) {
+      // keep the order "fetch step s+1, then multiply step s": the scheduler must not sink
+      // the LDS reads down to their first use
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(st, s + 1, (s + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_step(s & 1);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt + 1 < nk) {
+      // k-tiles kt+1 .. min(kt+NS-1, nk-1) are in flight; k-tile kt+1 must have landed.
+      // After the barrier it has for every wave, and every wave holds its last fragments of
+      // k-tile kt in registers, so this stage can be refilled with k-tile kt+NS.
+      const int later = nk - kt - 2;
+      wait_tiles(later < NS - 2 ? later : NS - 2);
+      __syncthreads();
+      if (kt + NS < nk) issue_loads(kt + NS, stage);
+      load_frags(smem + next * STAGE, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step((KS - 1) & 1);
+    stage = next;
   }
 
   // ---- epilogue: bias, activation, bf16, 8-byte stores ----------------------------------
@@ -265,13 +319,14 @@ __global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmAr
 
 // ---- host side --------------------------------------------------------------------------------
 
-using CfgA = TileCfg<256, 256, 64, 2, 4>;   // 8 waves, 128 KiB LDS, one workgroup per CU
-using CfgB = TileCfg<256, 256, 32, 2, 4>;   // 8 waves, 64 KiB LDS
-using CfgC = TileCfg<256, 128, 32, 2, 2>;   // 4 waves, 48 KiB LDS, two workgroups per CU
+using CfgA = TileCfg<256, 256, 64, 2, 4, 2>;   // 8 waves, 128 KiB LDS, one workgroup per CU
+using CfgB = TileCfg<256, 256, 32, 2, 4, 4>;   // 8 waves, 4 stages, 128 KiB LDS
+using CfgC = TileCfg<256, 128, 32, 2, 2, 3>;   // 4 waves, 3 stages, 72 KiB LDS, two workgroups per CU
+using CfgD = TileCfg<128, 256, 32, 2, 2, 3>;   // as C with the roles of rows and columns swapped
 
 // Tile configuration in use: set by scmoe_set_gemm_variant, else SCMOE_GEMM_VARIANT, else 0.
 static int g_variant = -1;
-constexpr int NUM_VARIANTS = 3;
+constexpr int NUM_VARIANTS = 4;
 
 static int gemm_variant() {
   if (g_variant < 0) {
@@ -299,13 +354,11 @@ static int launch_gemm(GemmArgs a, int max_rows, hipStream_t stream) {
     if (err != hipSuccess) return hip_fail(err);
     attr_set = true;
   }
-  int mtb = max_rows / CFG::BM + a.E;
-  mtb = ((mtb + CFG::GM - 1) / CFG::GM) * CFG::GM;
-  a.mtb = mtb;
+  // upper bound on row tiles: sum_e ceil(c_e / BM) <= max_rows / BM + E
+  const int mtb = max_rows / CFG::BM + a.E;
   a.nt = (a.N + CFG::BN - 1) / CFG::BN;
-  const int total = a.mtb * a.nt;
-  a.chunk = (total + 7) / 8;
-  hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT>), dim3(8 * a.chunk), dim3(CFG::THREADS), CFG::LDS_BYTES,
+  const int chunk = (mtb * a.nt + 7) / 8;
+  hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT>), dim3(8 * chunk), dim3(CFG::THREADS), CFG::LDS_BYTES,
                      stream, a);
   return launch_status();
 }
@@ -315,6 +368,7 @@ static int launch_variant(const GemmArgs& a, int max_rows, hipStream_t stream) {
   switch (gemm_variant()) {
     case 1: return launch_gemm<CfgB, ACT>(a, max_rows, stream);
     case 2: return launch_gemm<CfgC, ACT>(a, max_rows, stream);
+    case 3: return launch_gemm<CfgD, ACT>(a, max_rows, stream);
     default: return launch_gemm<CfgA, ACT>(a, max_rows, stream);
   }
 }
@@ -331,6 +385,7 @@ int ffn_mfma_bf16(const void* x, int64_t ldx, const int32_t* gather, const int32
   g1.gather = gather;
   g1.offsets = offsets;
   g1.W = static_cast<const unsigned char*>(W1);
+  g1.ldw = d;
   g1.bias = b1;
   g1.C = static_cast<unsigned char*>(hidden);
   g1.ldc = F;
@@ -346,6 +401,7 @@ int ffn_mfma_bf16(const void* x, int64_t ldx, const int32_t* gather, const int32
   g2.gather = nullptr;
   g2.offsets = offsets;
   g2.W = static_cast<const unsigned char*>(W2);
+  g2.ldw = F;
   g2.bias = b2;
   g2.C = static_cast<unsigned char*>(y);
   g2.ldc = ldy;
