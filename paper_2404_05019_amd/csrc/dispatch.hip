@@ -41,27 +41,38 @@ __global__ __launch_bounds__(DISP_BLOCK) void dispatch_hist(const int32_t* __res
   if (tid < E) blockhist[static_cast<int64_t>(blockIdx.x) * E + tid] = hist[tid];
 }
 
-// One workgroup.  Thread e walks the blocks in order.
-__global__ __launch_bounds__(64) void dispatch_scan(const int32_t* __restrict__ blockhist, int nblk,
-                                                    int E, int capacity,
-                                                    int32_t* __restrict__ blockbase,
-                                                    int32_t* __restrict__ counts,
-                                                    int32_t* __restrict__ offsets) {
+// One workgroup of four waves.  Each wave takes experts wave, wave+4, ...; its lanes take 64
+// consecutive blocks at a time and a shuffle scan gives the exclusive prefix over blocks.
+__global__ __launch_bounds__(256) void dispatch_scan(const int32_t* __restrict__ blockhist, int nblk,
+                                                     int E, int capacity,
+                                                     int32_t* __restrict__ blockbase,
+                                                     int32_t* __restrict__ counts,
+                                                     int32_t* __restrict__ offsets) {
   __shared__ int cnt[SCMOE_MAX_EXPERTS];
-  const int e = threadIdx.x;
-  if (e < E) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  for (int e = wave; e < E; e += 4) {
     int run = 0;
-    for (int b = 0; b < nblk; ++b) {
-      const int h = blockhist[static_cast<int64_t>(b) * E + e];
-      blockbase[static_cast<int64_t>(b) * E + e] = run;
-      run += h;
+    for (int b0 = 0; b0 < nblk; b0 += 64) {
+      const int b = b0 + lane;
+      const int h = (b < nblk) ? blockhist[static_cast<int64_t>(b) * E + e] : 0;
+      int incl = h;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += up;
+      }
+      if (b < nblk) blockbase[static_cast<int64_t>(b) * E + e] = run + incl - h;
+      run += __shfl(incl, 63, 64);
     }
-    const int c = run < capacity ? run : capacity;
-    cnt[e] = c;
-    counts[e] = c;
+    if (lane == 0) {
+      const int c = run < capacity ? run : capacity;
+      cnt[e] = c;
+      counts[e] = c;
+    }
   }
   __syncthreads();
-  if (e == 0) {
+  if (threadIdx.x == 0) {
     int run = 0;
     for (int q = 0; q < E; ++q) {
       offsets[q] = run;
@@ -168,7 +179,7 @@ int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, i
   int32_t* blockbase = blockhist + static_cast<size_t>(nblk) * E;
   if (nblk > 0)
     hipLaunchKernelGGL(dispatch_hist, dim3(nblk), dim3(DISP_BLOCK), 0, stream, expert_idx, T, k, E, blockhist);
-  hipLaunchKernelGGL(dispatch_scan, dim3(1), dim3(64), 0, stream, blockhist, nblk, E, capacity, blockbase,
+  hipLaunchKernelGGL(dispatch_scan, dim3(1), dim3(256), 0, stream, blockhist, nblk, E, capacity, blockbase,
                      counts, offsets);
   if (nblk > 0) {
     hipLaunchKernelGGL(dispatch_rank, dim3(nblk), dim3(DISP_BLOCK), 0, stream, expert_idx, T, k, E, capacity,

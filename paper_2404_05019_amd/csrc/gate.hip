@@ -3,29 +3,34 @@
 // The logits decide an integer (the arg max), so their arithmetic is fixed by the ABI:
 // fp32, one fused multiply-add per input feature in ascending feature order, then one
 // rounded add of the bias.  The kernel keeps that chain intact per (token, expert) and
-// finds its parallelism elsewhere: a workgroup owns 64 tokens, lane = token, and each wave
-// of the workgroup owns a contiguous group of EPL experts, so that the gate-matrix
-// operands are wave-uniform (scalar loads) and every lane runs EPL independent FMA chains.
-// x is staged through LDS in [64 tokens x 256 bytes] tiles so that HBM reads are coalesced
-// although each lane walks its own row.
+// finds its parallelism elsewhere: a workgroup owns 64 tokens, lane = token, and each of
+// its four waves owns a contiguous group of EPL experts, so every lane runs EPL independent
+// FMA chains.  x is staged through LDS in [64 tokens x 256 bytes] tiles (coalesced HBM
+// reads although each lane walks its own row; the next tile is prefetched into registers
+// while the current one is consumed), and so is the matching slab of W_g, which all lanes
+// of a wave then read at one address (an LDS broadcast).
 #include "common.hpp"
 
 namespace scmoe {
 
 constexpr int GATE_TOK = 64;            // tokens per workgroup (one per lane)
+constexpr int GATE_THREADS = 256;       // four waves
 constexpr int GATE_ROW_BYTES = 256;     // bytes of one token row staged per tile
-constexpr int GATE_ROW_STRIDE = 272;    // LDS row stride: +16 B keeps 16-lane reads conflict-free
-constexpr int GATE_LG_STRIDE = SCMOE_MAX_EXPERTS + 1;
+constexpr int GATE_ROW_STRIDE = 272;    // LDS row stride: +16 B keeps the row reads conflict-free
+constexpr int GATE_XV = GATE_TOK * 16 / GATE_THREADS;   // 16-byte pieces of x per thread and tile
 
 template <int EPL, bool BF16>
-__global__ __launch_bounds__(256) void gate_kernel(
+__global__ __launch_bounds__(GATE_THREADS) void gate_kernel(
     const unsigned char* __restrict__ x, int64_t ldx, const float* __restrict__ Wg,
     const float* __restrict__ bias, int T, int d, int E, int k, int normalize,
     int32_t* __restrict__ expert_idx, float* __restrict__ gate_w, float* __restrict__ probs) {
   constexpr int EB = BF16 ? 2 : 4;                 // element bytes
   constexpr int KC = GATE_ROW_BYTES / EB;          // features per tile
+  constexpr int EPAD = 4 * EPL;                    // expert columns held in LDS (zero padded)
+  constexpr int LGS = EPAD + 1;                    // row stride of the logit exchange buffer
   __shared__ __attribute__((aligned(16))) unsigned char xs[GATE_TOK * GATE_ROW_STRIDE];
-  __shared__ float lg[GATE_TOK * GATE_LG_STRIDE];
+  constexpr int WS_ELEMS = (KC * EPAD > GATE_TOK * LGS) ? KC * EPAD : GATE_TOK * LGS;
+  __shared__ __attribute__((aligned(16))) float ws[WS_ELEMS];    // reused for the logits at the end
   __shared__ float row_max[GATE_TOK];
   __shared__ float row_sum[GATE_TOK];
 
@@ -38,62 +43,89 @@ __global__ __launch_bounds__(256) void gate_kernel(
   float acc[EPL];
 #pragma unroll
   for (int j = 0; j < EPL; ++j) acc[j] = 0.0f;
-  // column of W_g each chain reads; chains past E read the last column and are discarded
-  int ecol[EPL];
+
+  // this thread's pieces of the x tile: piece c = tid + u*256 -> row c/16, 16-byte column c%16
+  const unsigned char* src[GATE_XV];
 #pragma unroll
-  for (int j = 0; j < EPL; ++j) ecol[j] = (e0 + j < E) ? e0 + j : E - 1;
+  for (int u = 0; u < GATE_XV; ++u) {
+    const int c = tid + u * GATE_THREADS;
+    int t = t0 + (c >> 4);
+    if (t >= T) t = T - 1;
+    src[u] = x + static_cast<int64_t>(t) * ldx * EB + (c & 15) * 16;
+  }
+  uint4 pre[GATE_XV];
+  auto fetch = [&](int kc0) {
+    const int nvec = ((d - kc0 < KC) ? d - kc0 : KC) * EB / 16;
+#pragma unroll
+    for (int u = 0; u < GATE_XV; ++u)
+      if (((tid + u * GATE_THREADS) & 15) < nvec)
+        pre[u] = *reinterpret_cast<const uint4*>(src[u] + static_cast<int64_t>(kc0) * EB);
+  };
+  fetch(0);
 
   for (int kc0 = 0; kc0 < d; kc0 += KC) {
     const int kn = (d - kc0 < KC) ? d - kc0 : KC;  // features in this tile (multiple of 8)
-    const int nvec = kn * EB / 16;                 // 16-byte chunks per row
-    __syncthreads();
-    for (int c = tid; c < GATE_TOK * 16; c += blockDim.x) {
-      const int row = c >> 4, col = c & 15;
-      if (col < nvec) {
-        int t = t0 + row;
-        if (t >= T) t = T - 1;
-        const uint4 v = *reinterpret_cast<const uint4*>(x + (static_cast<int64_t>(t) * ldx + kc0) * EB + col * 16);
-        *reinterpret_cast<uint4*>(xs + row * GATE_ROW_STRIDE + col * 16) = v;
-      }
+    const int nvec = kn * EB / 16;                 // 16-byte pieces per row
+    __syncthreads();                               // the previous tile has been consumed
+#pragma unroll
+    for (int u = 0; u < GATE_XV; ++u) {
+      const int c = tid + u * GATE_THREADS;
+      if ((c & 15) < nvec) *reinterpret_cast<uint4*>(xs + (c >> 4) * GATE_ROW_STRIDE + (c & 15) * 16) = pre[u];
+    }
+    for (int c = tid; c < kn * EPAD; c += GATE_THREADS) {
+      const int i = c / EPAD, e = c - i * EPAD;
+      ws[c] = (e < E) ? Wg[static_cast<int64_t>(kc0 + i) * E + e] : 0.0f;
     }
     __syncthreads();
-    const unsigned char* myrow = xs + lane * GATE_ROW_STRIDE;
-    for (int c = 0; c < nvec; ++c) {
-      const uint4 v = *reinterpret_cast<const uint4*>(myrow + c * 16);
-      const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
-      if (BF16) {
-        const float* wrow = Wg + static_cast<int64_t>(kc0 + c * 8) * E;
+    if (kc0 + KC < d) fetch(kc0 + KC);             // in flight while this tile is consumed
+    if (e0 < E) {
+      const unsigned char* myrow = xs + lane * GATE_ROW_STRIDE;
+      constexpr int XPV = 16 / EB;                 // features per 16-byte piece
+      for (int c = 0; c < nvec; ++c) {
+        const uint4 v = *reinterpret_cast<const uint4*>(myrow + c * 16);
+        const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+        const float* wrow = ws + (c * XPV) * EPAD + e0;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          const uint32_t word = wd[q >> 1];
-          const float xv = __uint_as_float((q & 1) ? (word & 0xffff0000u) : (word << 16));
+        for (int q = 0; q < XPV; ++q) {
+          float xv;
+          if (BF16) {
+            const uint32_t word = wd[q >> 1];
+            xv = __uint_as_float((q & 1) ? (word & 0xffff0000u) : (word << 16));
+          } else {
+            xv = __uint_as_float(wd[q]);
+          }
+          float wv[EPL];
+          if (EPL >= 4) {
 #pragma unroll
-          for (int j = 0; j < EPL; ++j) acc[j] = __fmaf_rn(xv, wrow[q * E + ecol[j]], acc[j]);
-        }
-      } else {
-        const float* wrow = Wg + static_cast<int64_t>(kc0 + c * 4) * E;
+            for (int j = 0; j < EPL; j += 4) {
+              const float4 f = *reinterpret_cast<const float4*>(wrow + q * EPAD + j);
+              wv[j] = f.x; wv[j + 1] = f.y; wv[j + 2] = f.z; wv[j + 3] = f.w;
+            }
+          } else {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float xv = __uint_as_float(wd[q]);
+            for (int j = 0; j < EPL; ++j) wv[j] = wrow[q * EPAD + j];
+          }
 #pragma unroll
-          for (int j = 0; j < EPL; ++j) acc[j] = __fmaf_rn(xv, wrow[q * E + ecol[j]], acc[j]);
+          for (int j = 0; j < EPL; ++j) acc[j] = __fmaf_rn(xv, wv[j], acc[j]);
         }
       }
     }
   }
+  __syncthreads();                                 // ws is free: reuse it for the logits
+  float* lg = ws;
 #pragma unroll
   for (int j = 0; j < EPL; ++j) {
     if (e0 + j < E) {
       float v = acc[j];
       if (bias != nullptr) v = __fadd_rn(v, bias[e0 + j]);
-      lg[lane * GATE_LG_STRIDE + e0 + j] = v;
+      lg[lane * LGS + e0 + j] = v;
     }
   }
   __syncthreads();
 
   if (wave == 0) {
     const int t = t0 + lane;
-    const float* l = lg + lane * GATE_LG_STRIDE;
+    const float* l = lg + lane * LGS;
     int sel0 = 0, sel1 = -1;
     for (int e = 1; e < E; ++e) {
       const float v = l[e], b = l[sel0];
@@ -135,9 +167,9 @@ __global__ __launch_bounds__(256) void gate_kernel(
   if (probs != nullptr) {
     __syncthreads();
     const int ntok = (T - t0 < GATE_TOK) ? T - t0 : GATE_TOK;
-    for (int c = tid; c < ntok * E; c += blockDim.x) {
+    for (int c = tid; c < ntok * E; c += GATE_THREADS) {
       const int tok = c / E, e = c - tok * E;
-      probs[static_cast<int64_t>(t0) * E + c] = expf(lg[tok * GATE_LG_STRIDE + e] - row_max[tok]) / row_sum[tok];
+      probs[static_cast<int64_t>(t0) * E + c] = expf(lg[tok * LGS + e] - row_max[tok]) / row_sum[tok];
     }
   }
 }
@@ -146,8 +178,7 @@ template <int EPL>
 static void launch_gate(int dtype, const void* x, int64_t ldx, const float* Wg, const float* bias,
                         int T, int d, int E, int k, int normalize, int32_t* idx, float* gw,
                         float* probs, hipStream_t stream) {
-  const int nwaves = (E + EPL - 1) / EPL;
-  dim3 grid((T + GATE_TOK - 1) / GATE_TOK), block(64 * nwaves);
+  dim3 grid((T + GATE_TOK - 1) / GATE_TOK), block(GATE_THREADS);
   const unsigned char* xb = static_cast<const unsigned char*>(x);
   if (dtype == SCMOE_BF16)
     hipLaunchKernelGGL((gate_kernel<EPL, true>), grid, block, 0, stream, xb, ldx, Wg, bias, T, d, E, k,
@@ -168,7 +199,7 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
   if (T == 0) return SCMOE_OK;
   if (!x || !Wg || !idx || !gw) return SCMOE_ERR_NULL;
   if (!view_ok(x, ldx, d, dtype)) return SCMOE_ERR_SHAPE;
-  // experts per wave: at most four waves per workgroup
+  // experts per wave (four waves per workgroup)
   if (E <= 4) launch_gate<1>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream);
   else if (E <= 8) launch_gate<2>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream);
   else if (E <= 16) launch_gate<4>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream);
