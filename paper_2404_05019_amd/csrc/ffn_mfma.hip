@@ -7,17 +7,19 @@
 // layout v_mfma_f32_32x32x16_bf16 wants: each lane feeds 8 consecutive k of one row.
 //
 // Design (gfx950):
-//  * A workgroup owns a BM x BN output tile of ONE expert.  Tiles are enumerated on the
-//    device from offsets[] (no host round trip); surplus workgroups exit at once.
+//  * Persistent workgroups; each takes BM x BN output tiles (one expert per tile) from a
+//    schedule derived on the device from offsets[] (no host round trip), and requests the
+//    first k-tiles of its next tile before it runs the epilogue of the current one.
 //  * Global -> LDS copies use the direct-to-LDS form of the global load (16 bytes per
 //    lane, no VGPR staging).  Such a load writes 1 KiB of consecutive LDS per wave, so the
 //    bank-conflict swizzle is applied on the global side: the lane that fills LDS slot
 //    (row, c) fetches k-chunk  c ^ swz(row)  of that row.
-//  * LDS is double buffered and the register fragments are double buffered too: global
-//    loads run one k-tile ahead, LDS reads one k16-step ahead of the MFMAs; one workgroup
+//  * N LDS stages and double-buffered register fragments: global loads run N-1 k-tiles
+//    ahead, LDS reads one k16-step ahead, issued one behind each MFMA; one workgroup
 //    barrier per k-tile.
 //  * The MFMA is issued with the weight fragment as its first operand, so a lane ends up
-//    holding 4 consecutive output columns of one row and stores them as one 8-byte piece.
+//    holding 4 consecutive output columns of one row; the epilogue re-assembles rows in a
+//    small per-wave LDS patch and stores whole 128-byte lines.
 //  * Workgroup ids are remapped so that each XCD (ids congruent mod 8 land on one XCD and
 //    share its L2) walks a compact block of neighbouring tiles.
 //  * Rows can be gathered on load through an index array (the dispatch permutation), which
@@ -107,77 +109,92 @@ struct TileCfg {
   static constexpr int RPL = 64 / CPR;                   // rows filled by one wave-wide load
   static constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB, STAGE = A_BYTES + B_BYTES;
   static constexpr int A_PER_WAVE = BM / RPL / WAVES, B_PER_WAVE = BN / RPL / WAVES;
-  static constexpr int LDS_BYTES = NS * STAGE;
+  static constexpr int STG_ROW = TN * 2;                  // bytes of one row of a wave's epilogue staging patch
+  static constexpr int STG_ROWS = (WAVES == 8) ? 32 : 16; // rows staged at a time (LDS budget)
+  static constexpr int STG_BYTES = STG_ROWS * STG_ROW;
+  static constexpr int LDS_BYTES = NS * STAGE + WAVES * STG_BYTES;
   // workgroups of this shape that fit one CU (512 VGPRs per SIMD lane, 160 KiB LDS)
   static constexpr int WG_PER_CU = (160 * 1024 / LDS_BYTES) < (8 / WAVES) ? (160 * 1024 / LDS_BYTES) : (8 / WAVES);
   static constexpr int GM = 4;                           // row tiles per raster group
   static_assert(BM % (RPL * WAVES) == 0 && BN % (RPL * WAVES) == 0, "loads must divide evenly");
-  static_assert(TM % 32 == 0 && TN % 32 == 0 && (BK == 32 || BK == 64) && NS >= 2 && NS <= 4, "tile shape");
+  static_assert(TM % 32 == 0 && TN == 64 && (BK == 32 || BK == 64) && NS >= 2 && NS <= 4, "tile shape");
+  static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024 && WG_PER_CU >= 1, "LDS budget");
 };
 
 template <class CFG, bool ACT>
-__global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmArgs p) {
+__global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void gemm_bf16_kernel(const GemmArgs p) {
   constexpr int BM = CFG::BM, BN = CFG::BN, BK = CFG::BK, RB = CFG::RB, CPR = CFG::CPR;
   constexpr int MI = CFG::MI, NJ = CFG::NJ, STAGE = CFG::STAGE, A_BYTES = CFG::A_BYTES;
+  constexpr int NS = CFG::NS;
+  constexpr int KS = BK / 16;                                   // k16-steps per k-tile (even)
+  constexpr int LPW = CFG::A_PER_WAVE + CFG::B_PER_WAVE;        // direct loads per wave and k-tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-  // ---- which tile? ----------------------------------------------------------------------
-  // Row tiles are counted from offsets[] here, so that the eight XCDs get equal shares of
-  // the tiles that really exist (the grid is sized for an upper bound).  Workgroup ids
-  // congruent mod 8 run on one XCD; each XCD walks a contiguous range of the raster order
-  // "GM row tiles x all column tiles", which keeps its L2 working set compact.
+  // ---- tile schedule ------------------------------------------------------------------------
+  // Persistent workgroups.  Row tiles are counted from offsets[] on the device (no host round
+  // trip).  Workgroup ids congruent mod 8 run on one XCD; XCD x owns the contiguous range
+  // [x*chunk, (x+1)*chunk) of the raster order "GM row tiles x all column tiles", and its
+  // workgroups take tiles of that range round-robin, so the tiles in flight on one XCD are
+  // neighbours and share A and W panels in its L2.
   int mt_total = 0;
   for (int q = 0; q < p.E; ++q) mt_total += (p.offsets[q + 1] - p.offsets[q] + BM - 1) / BM;
   const int total = mt_total * p.nt;
   const int chunk = (total + 7) >> 3;
-  const int bid = blockIdx.x;
-  const int L = (bid & 7) * chunk + (bid >> 3);
-  if ((bid >> 3) >= chunk || L >= total) return;
-  const int grp = L / (CFG::GM * p.nt);
-  const int rem = L - grp * CFG::GM * p.nt;
-  const int grows = (mt_total - grp * CFG::GM < CFG::GM) ? mt_total - grp * CFG::GM : CFG::GM;
-  int mt = grp * CFG::GM + rem % grows;
-  const int n0 = (rem / grows) * BN;
-  int e = 0, row0 = 0, row_end = 0;
-  for (e = 0; e < p.E; ++e) {
-    const int s = p.offsets[e];
-    const int c = p.offsets[e + 1] - s;
-    const int ntile = (c + BM - 1) / BM;
-    if (mt < ntile) {
-      row0 = s + mt * BM;
-      row_end = s + c;
-      break;
+  const int nslots = gridDim.x >> 3;
+  int L = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
+  const int Lend = (((blockIdx.x & 7) + 1) * chunk < total) ? ((blockIdx.x & 7) + 1) * chunk : total;
+  if (L >= Lend) return;
+
+  // tile L -> expert e, packed rows [row0, row_end) (row0 + BM may exceed row_end), column n0
+  auto locate = [&](int l, int& e, int& row0, int& row_end, int& n0) {
+    const int grp = l / (CFG::GM * p.nt);
+    const int rem = l - grp * CFG::GM * p.nt;
+    const int grows = (mt_total - grp * CFG::GM < CFG::GM) ? mt_total - grp * CFG::GM : CFG::GM;
+    int mt = grp * CFG::GM + rem % grows;
+    n0 = (rem / grows) * BN;
+    row0 = 0;
+    row_end = 1;
+    for (e = 0; e < p.E; ++e) {
+      const int s = p.offsets[e];
+      const int c = p.offsets[e + 1] - s;
+      const int ntile = (c + BM - 1) / BM;
+      if (mt < ntile) {
+        row0 = s + mt * BM;
+        row_end = s + c;
+        break;
+      }
+      mt -= ntile;
     }
-    mt -= ntile;
-  }
-  if (e == p.E) return;   // not reachable: mt < mt_total
+    if (e == p.E) e = p.E - 1;   // not reachable for l < total
+  };
 
   // ---- per-lane source addresses of the direct-to-LDS loads -------------------------------
-  const unsigned char* We = p.W + static_cast<int64_t>(e) * p.N * p.ldw * 2;
   const unsigned char* aptr[CFG::A_PER_WAVE];
   const unsigned char* bptr[CFG::B_PER_WAVE];
+  auto set_ptrs = [&](int e, int row0, int row_end, int n0) {
+    const unsigned char* We = p.W + static_cast<int64_t>(e) * p.N * p.ldw * 2;
 #pragma unroll
-  for (int i = 0; i < CFG::A_PER_WAVE; ++i) {
-    const int row = (wave * CFG::A_PER_WAVE + i) * CFG::RPL + lane / CPR;
-    const int kc = (lane % CPR) ^ swz<CPR>(row);
-    int m = row0 + row;
-    if (m > row_end - 1) m = row_end - 1;        // rows past the segment re-read its last row
-    const int64_t src = p.gather ? p.gather[m] : m;
-    aptr[i] = p.A + src * p.lda * 2 + kc * 16;
-  }
+    for (int i = 0; i < CFG::A_PER_WAVE; ++i) {
+      const int row = (wave * CFG::A_PER_WAVE + i) * CFG::RPL + lane / CPR;
+      const int kc = (lane % CPR) ^ swz<CPR>(row);
+      int m = row0 + row;
+      if (m > row_end - 1) m = row_end - 1;      // rows past the segment re-read its last row
+      const int64_t src = p.gather ? p.gather[m] : m;
+      aptr[i] = p.A + src * p.lda * 2 + kc * 16;
+    }
 #pragma unroll
-  for (int i = 0; i < CFG::B_PER_WAVE; ++i) {
-    const int row = (wave * CFG::B_PER_WAVE + i) * CFG::RPL + lane / CPR;
-    const int kc = (lane % CPR) ^ swz<CPR>(row);
-    int n = n0 + row;
-    if (n > p.N - 1) n = p.N - 1;
-    bptr[i] = We + static_cast<int64_t>(n) * p.ldw * 2 + kc * 16;
-  }
-
+    for (int i = 0; i < CFG::B_PER_WAVE; ++i) {
+      const int row = (wave * CFG::B_PER_WAVE + i) * CFG::RPL + lane / CPR;
+      const int kc = (lane % CPR) ^ swz<CPR>(row);
+      int n = n0 + row;
+      if (n > p.N - 1) n = p.N - 1;
+      bptr[i] = We + static_cast<int64_t>(n) * p.ldw * 2 + kc * 16;
+    }
+  };
   auto issue_loads = [&](int kt, int stage) {
     unsigned char* sa = smem + stage * STAGE + wave * CFG::A_PER_WAVE * 1024;
     unsigned char* sb = smem + stage * STAGE + A_BYTES + wave * CFG::B_PER_WAVE * 1024;
@@ -190,8 +207,21 @@ __global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmAr
       __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(bptr[i] + static_cast<int64_t>(kt) * RB),
                                        SCMOE_LDS_PTR(sb + i * 1024), 16, 0, 0);
   };
+  const int nk = p.Kd / BK;
+  auto issue_prologue = [&]() {
+#pragma unroll
+    for (int t = 0; t < NS; ++t)
+      if (t < nk) issue_loads(t, t);
+  };
+  // wait until at most `tiles` of the newest k-tiles are still in flight (loads complete in
+  // issue order, LPW loads per k-tile and wave)
+  auto wait_tiles = [&](int tiles) {
+    if (tiles >= 2) __builtin_amdgcn_s_waitcnt(((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14) | 0x0F70);
+    else if (tiles == 1) __builtin_amdgcn_s_waitcnt((LPW & 15) | ((LPW >> 4) << 14) | 0x0F70);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+  };
 
-  // ---- fragment read offsets ---------------------------------------------------------------
+  // ---- fragment read offsets (the same for every tile) --------------------------------------
   const int wave_m = wave / CFG::WN, wave_n = wave % CFG::WN;
   const int lr = lane & 31, lh = lane >> 5;
   int xoff[MI], woff[NJ];   // byte offset of (row, chunk lh) for k16-step 0, swizzled
@@ -207,21 +237,9 @@ __global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmAr
   }
 
   f32x16_t acc[MI][NJ];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-  // Software pipeline.  Global -> LDS: two k-tiles in flight (one per LDS stage).  LDS ->
-  // registers: the fragments of k16-step s+1 are fetched while the MFMAs of step s issue,
-  // and the first fragments of the next k-tile are fetched (after the one barrier per
-  // k-tile) under the MFMAs of the last step, so no MFMA waits on an LDS round trip.
-  constexpr int KS = BK / 16;                                   // k16-steps per k-tile (even)
-  constexpr int LPW = CFG::A_PER_WAVE + CFG::B_PER_WAVE;        // direct loads per wave and k-tile
   bf16x8_t xf[2][MI], wf[2][NJ];
   auto load_frags = [&](const unsigned char* st, int s, int buf) {
+    // k16-step s reads chunks 2s and 2s+1: an XOR on the swizzled chunk index
 #pragma unroll
     for (int i = 0; i < MI; ++i)
       xf[buf][i] = *reinterpret_cast<const bf16x8_t*>(st + (xoff[i] ^ (s << 5)));
@@ -237,83 +255,126 @@ __global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmAr
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[i][j], 0, 0, 0);
   };
 
-  const int nk = p.Kd / BK;
-  constexpr int NS = CFG::NS;
-  // wait until at most `tiles` of the newest k-tiles are still in flight (loads complete in
-  // issue order, LPW loads per k-tile and wave)
-  auto wait_tiles = [&](int tiles) {
-    if (tiles >= 2) __builtin_amdgcn_s_waitcnt(((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14) | 0x0F70);
-    else if (tiles == 1) __builtin_amdgcn_s_waitcnt((LPW & 15) | ((LPW >> 4) << 14) | 0x0F70);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
-  };
+  int e, row0, row_end, n0;
+  locate(L, e, row0, row_end, n0);
+  set_ptrs(e, row0, row_end, n0);
+  issue_prologue();
+  bool first = true;
+  for (;;) {
 #pragma unroll
-  for (int t = 0; t < NS; ++t)
-    if (t < nk) issue_loads(t, t);
-  wait_tiles((nk < NS ? nk : NS) - 1);
-  __syncthreads();
-  load_frags(smem, 0, 0);
-  int stage = 0;                      // kt % NS
-  for (int kt = 0; kt < nk; ++kt) {
-    const unsigned char* st = smem + stage * STAGE;
-    const int next = (stage + 1 == NS) ? 0 : stage + 1;
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int s = 0; s + 1 < KS; ++s) {
-      // keep the order "fetch step s+1, then multiply step s": the scheduler must not sink
-      // the LDS reads down to their first use
-      __builtin_amdgcn_sched_barrier(0);
-      load_frags(st, s + 1, (s + 1) & 1);
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_step(s & 1);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (kt + 1 < nk) {
-      // k-tiles kt+1 .. min(kt+NS-1, nk-1) are in flight; k-tile kt+1 must have landed.
-      // After the barrier it has for every wave, and every wave holds its last fragments of
-      // k-tile kt in registers, so this stage can be refilled with k-tile kt+NS.
-      const int later = nk - kt - 2;
-      wait_tiles(later < NS - 2 ? later : NS - 2);
-      __syncthreads();
-      if (kt + NS < nk) issue_loads(kt + NS, stage);
-      load_frags(smem + next * STAGE, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_step((KS - 1) & 1);
-    stage = next;
-  }
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  // ---- epilogue: bias, activation, bf16, 8-byte stores ----------------------------------
-  // acc[i][j][v] is output row (lane & 31) of row-subtile i and column
-  // 8*(v/4) + 4*(lane/32) + v%4 of column-subtile j.
-  const float* bias_e = p.bias ? p.bias + static_cast<int64_t>(e) * p.N : nullptr;
+    // ---- main loop ---------------------------------------------------------------------------
+    // Global -> LDS runs NS-1 k-tiles ahead; LDS -> registers runs one k16-step ahead, each
+    // ds_read slotted behind an MFMA; one workgroup barrier per k-tile.  After an epilogue
+    // the stores of the previous tile share the counter with the loads, so everything is
+    // waited for (the prologue loads had the whole epilogue to land).
+    if (first) wait_tiles((nk < NS ? nk : NS) - 1);
+    else wait_tiles(0);
+    __syncthreads();
+    load_frags(smem, 0, 0);
+    int stage = 0;                      // kt % NS
+    for (int kt = 0; kt < nk; ++kt) {
+      const unsigned char* st = smem + stage * STAGE;
+      const int next = (stage + 1 == NS) ? 0 : stage + 1;
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    const int m = row0 + wave_m * CFG::TM + i * 32 + lr;
-    if (m >= row_end) continue;
-    unsigned char* crow = p.C + static_cast<int64_t>(m) * p.ldc * 2;
+      for (int s = 0; s + 1 < KS; ++s) {
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(st, s + 1, (s + 1) & 1);
+        mfma_step(s & 1);
+        // issue order: MFMA, ds_read, MFMA, ds_read, ... (the reads feed the NEXT step)
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wave_n * CFG::TN + j * 32 + 8 * g + 4 * lh;
-        if (n >= p.N) continue;
-        float v[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = acc[i][j][4 * g + q];
-        if (bias_e) {
-          const float4 b = *reinterpret_cast<const float4*>(bias_e + n);
-          v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
+        for (int q = 0; q < MI + NJ; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        if (ACT) {
+        __builtin_amdgcn_sched_group_barrier(0x008, MI * NJ - (MI + NJ), 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (kt + 1 < nk) {
+        // k-tiles kt+1 .. min(kt+NS-1, nk-1) are in flight; k-tile kt+1 must have landed.
+        // After the barrier it has for every wave, and every wave holds its last fragments
+        // of k-tile kt in registers, so this stage can be refilled with k-tile kt+NS.
+        const int later = nk - kt - 2;
+        wait_tiles(later < NS - 2 ? later : NS - 2);
+        __syncthreads();
+        if (kt + NS < nk) issue_loads(kt + NS, stage);
+        load_frags(smem + next * STAGE, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_step((KS - 1) & 1);
+      stage = next;
+    }
+
+    // ---- next tile: its first k-tiles are requested before this tile's epilogue -----------
+    const int Ln = L + nslots;
+    const bool more = Ln < Lend;
+    const int ce = e, crow0 = row0, crow_end = row_end, cn0 = n0;
+    __syncthreads();                    // every wave holds its last fragments: LDS is free
+    if (more) {
+      locate(Ln, e, row0, row_end, n0);
+      set_ptrs(e, row0, row_end, n0);
+      issue_prologue();
+    }
+
+    // ---- epilogue: bias, activation, bf16; rows re-assembled in LDS, 16-byte stores ---------
+    // acc[i][j][v] is output row (lane & 31) of row-subtile i and column
+    // 8*(v/4) + 4*(lane/32) + v%4 of column-subtile j.  A wave stages one 32-row slab of its
+    // tile in its private LDS patch and writes it out with TN/8 lanes per row, so that every
+    // store instruction covers whole 128-byte lines.
+    const float* bias_e = p.bias ? p.bias + static_cast<int64_t>(ce) * p.N : nullptr;
+    unsigned char* stg = smem + NS * STAGE + wave * CFG::STG_BYTES;
 #pragma unroll
-          for (int q = 0; q < 4; ++q)
-            v[q] = (p.gelu_mode == SCMOE_GELU_TANH) ? gelu_tanh_fast(v[q]) : gelu_erf_fast(v[q]);
+    for (int i = 0; i < MI; ++i) {
+      const int mbase = crow0 + wave_m * CFG::TM + i * 32;
+      if (mbase >= crow_end) continue;          // wave-uniform: the whole slab is past the segment
+#pragma unroll
+      for (int h = 0; h < 32 / CFG::STG_ROWS; ++h) {
+        const int sr = lr - h * CFG::STG_ROWS;  // this lane's row inside the staged rows
+        const bool mine = sr >= 0 && sr < CFG::STG_ROWS;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int n = cn0 + wave_n * CFG::TN + j * 32 + 8 * g + 4 * lh;
+            float v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = acc[i][j][4 * g + q];
+            if (bias_e && n < p.N) {
+              const float4 b = *reinterpret_cast<const float4*>(bias_e + n);
+              v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
+            }
+            if (ACT) {
+#pragma unroll
+              for (int q = 0; q < 4; ++q)
+                v[q] = (p.gelu_mode == SCMOE_GELU_TANH) ? gelu_tanh_fast(v[q]) : gelu_erf_fast(v[q]);
+            }
+            uint2 o;
+            o.x = cvt_pk_bf16(v[0], v[1]);
+            o.y = cvt_pk_bf16(v[2], v[3]);
+            // 16-byte chunk 4j+g of the row, swizzled like the operand tiles; half lh of it
+            if (mine) *reinterpret_cast<uint2*>(stg + sr * CFG::STG_ROW + (((4 * j + g) ^ swz<8>(sr)) << 4) + lh * 8) = o;
+          }
         }
-        uint2 o;
-        o.x = cvt_pk_bf16(v[0], v[1]);
-        o.y = cvt_pk_bf16(v[2], v[3]);
-        *reinterpret_cast<uint2*>(crow + static_cast<int64_t>(n) * 2) = o;
+#pragma unroll
+        for (int r0 = 0; r0 < CFG::STG_ROWS; r0 += 8) {
+          const int r = r0 + (lane >> 3);       // 8 lanes of 16 bytes per 128-byte row
+          const int c = lane & 7;
+          const uint4 o = *reinterpret_cast<const uint4*>(stg + r * CFG::STG_ROW + ((c ^ swz<8>(r)) << 4));
+          const int m = mbase + h * CFG::STG_ROWS + r;
+          const int n = cn0 + wave_n * CFG::TN + c * 8;
+          if (m < crow_end && n < p.N)
+            *reinterpret_cast<uint4*>(p.C + (static_cast<int64_t>(m) * p.ldc + n) * 2) = o;
+        }
       }
     }
+    if (!more) break;
+    L = Ln;
+    first = false;
   }
 }
 
@@ -322,11 +383,10 @@ __global__ __launch_bounds__(CFG::THREADS, 2) void gemm_bf16_kernel(const GemmAr
 using CfgA = TileCfg<256, 256, 64, 2, 4, 2>;   // 8 waves, 128 KiB LDS, one workgroup per CU
 using CfgB = TileCfg<256, 256, 32, 2, 4, 4>;   // 8 waves, 4 stages, 128 KiB LDS
 using CfgC = TileCfg<256, 128, 32, 2, 2, 3>;   // 4 waves, 3 stages, 72 KiB LDS, two workgroups per CU
-using CfgD = TileCfg<128, 256, 32, 2, 2, 3>;   // as C with the roles of rows and columns swapped
 
 // Tile configuration in use: set by scmoe_set_gemm_variant, else SCMOE_GEMM_VARIANT, else 0.
 static int g_variant = -1;
-constexpr int NUM_VARIANTS = 4;
+constexpr int NUM_VARIANTS = 3;
 
 static int gemm_variant() {
   if (g_variant < 0) {
@@ -345,6 +405,19 @@ int set_gemm_variant(int v) {
 
 bool ffn_mfma_supported(int d, int F) { return d > 0 && F > 0 && (d % 64) == 0 && (F % 64) == 0; }
 
+// Compute units of the current device (256 on MI355X), cached per device.
+static int num_cus() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 template <class CFG, bool ACT>
 static int launch_gemm(GemmArgs a, int max_rows, hipStream_t stream) {
   static bool attr_set = false;
@@ -357,8 +430,10 @@ static int launch_gemm(GemmArgs a, int max_rows, hipStream_t stream) {
   // upper bound on row tiles: sum_e ceil(c_e / BM) <= max_rows / BM + E
   const int mtb = max_rows / CFG::BM + a.E;
   a.nt = (a.N + CFG::BN - 1) / CFG::BN;
-  const int chunk = (mtb * a.nt + 7) / 8;
-  hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT>), dim3(8 * chunk), dim3(CFG::THREADS), CFG::LDS_BYTES,
+  int slots = (mtb * a.nt + 7) / 8;                            // tiles per XCD, upper bound
+  const int resident = (num_cus() / 8) * CFG::WG_PER_CU;       // workgroups one XCD holds at once
+  if (slots > resident) slots = resident;
+  hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT>), dim3(8 * slots), dim3(CFG::THREADS), CFG::LDS_BYTES,
                      stream, a);
   return launch_status();
 }
@@ -368,7 +443,6 @@ static int launch_variant(const GemmArgs& a, int max_rows, hipStream_t stream) {
   switch (gemm_variant()) {
     case 1: return launch_gemm<CfgB, ACT>(a, max_rows, stream);
     case 2: return launch_gemm<CfgC, ACT>(a, max_rows, stream);
-    case 3: return launch_gemm<CfgD, ACT>(a, max_rows, stream);
     default: return launch_gemm<CfgA, ACT>(a, max_rows, stream);
   }
 }

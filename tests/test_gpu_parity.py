@@ -169,7 +169,7 @@ def test_expert_ffn_parity(oracle, E, lens, d, F, dtype, biases, gelu_mode):
     _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2])
 def test_expert_ffn_tile_variants(oracle, variant):
     """Every tile configuration of the MFMA grouped GEMM meets the same bar."""
     B.scmoe_set_gemm_variant(variant)
