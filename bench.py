@@ -18,6 +18,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+# Memory traffic of one grouped-GEMM launch (bytes), from two rocprofv3 --pmc passes
+# (FETCH_SIZE, WRITE_SIZE) scaled by a 1 GiB copy in the same run: see
+# profiles/gemm_bf16_kernel_large_pmc.txt.  Only measured for the workload it is keyed by.
+GEMM_TRAFFIC_BYTES = {"large": 2.53e9}
 
 
 def parse():
@@ -31,6 +35,8 @@ def parse():
     ap.add_argument("--gemm-variant", type=int, default=None)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -114,6 +120,16 @@ def main():
                                                            y_perm), args.steps, 2)
     ms_comb = time_region(torch, lambda: B.scmoe_combine(y_perm, dst_row, gw, 1, s_out, None, None, y), n_ops, 3)
 
+    if args.calibrate_copy:
+        # plain copy of known size: 1 GiB read + 1 GiB written per launch, far larger than the
+        # 256 MB last-level cache, so the HBM byte counters of this kernel give their scale
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=DEV).fill_(1)
+        dst = torch.empty(1 << 30, dtype=torch.uint8, device=DEV)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # algorithmic work per unit (kept row / token) of each operator
     ffn_flops = 4.0 * K * d * F                       # two GEMMs of 2*K*d*F each
     gate_bytes = T * (d * eb + 8)
@@ -128,7 +144,8 @@ def main():
         "peak": PEAK_BF16_TFLOPS if is_mfma else 78.6,
         "unit": "TFLOP/s",
         "frac": round(ach_tflops / (PEAK_BF16_TFLOPS if is_mfma else 78.6), 4),
-        "traffic": None,
+        "traffic": GEMM_TRAFFIC_BYTES.get(args.workload),
+        "algorithmic_bytes_per_launch": (2 * K * d + 2 * (E + 0) * d * F + K * F) * eb / 2 + K * F * eb / 2,
         "flops_per_launch": ffn_flops / 2,
         "avg_launch_ms": round(ms_ffn / 2, 4),
         "launches_per_call": 2,
