@@ -67,8 +67,8 @@ typedef struct scmoe_desc {
   int32_t d;         /* model width                                                   */
   int32_t F;         /* FFN hidden width                                              */
   int32_t E;         /* routed experts, 1..SCMOE_MAX_EXPERTS                          */
-  int32_t k;         /* experts per token: 1 for scmoe_layer_forward, 1 or 2 for the
-                        standard layer                                                */
+  int32_t k;         /* routed experts per token, 1 or 2 (ScMoE proper uses 1; 2 with the
+                        shared expert is the ScMoE-2 variant of the appendix)          */
   int32_t capacity;  /* C: rows an expert accepts; >= T*k means unbounded             */
   int32_t dtype;     /* SCMOE_F32 / SCMOE_BF16                                        */
   int32_t gelu_mode; /* SCMOE_GELU_ERF / SCMOE_GELU_TANH                              */
@@ -237,12 +237,14 @@ int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out);
  *
  *   y = SE(x_cur) + sum_i G(x_prev)_i E_i(x_prev)
  *
- * = gate_top1(x_prev) -> dispatch -> expert_ffn -> combine(base = SE(x_cur)).
+ * = gate(x_prev) -> dispatch -> expert_ffn -> combine(base = SE(x_cur)).
  * The shared expert depends on x_cur only and the routed chain on x_prev only (Sec. 3.2):
  * with stream_aux != NULL the shared expert's GEMMs are enqueued on stream_aux and the
  * routed chain on stream_main, forked and joined with events; with stream_aux == NULL
  * everything runs in order on stream_main.  The result is ready on stream_main.
- * desc->k must be 1.  With desc->cg_mode != 0 the coefficient gate reads x_cur.
+ * desc->k = 1 is ScMoE; desc->k = 2 routes two experts per token on x_prev (ScMoE-2,
+ * appendix "more activated experts").  With desc->cg_mode != 0 the coefficient gate reads
+ * x_cur.
  * residual may be NULL.  routing may be NULL.  No host synchronisation happens inside.
  */
 int scmoe_layer_forward(const scmoe_desc* desc, const void* x_prev, int64_t ld_prev,

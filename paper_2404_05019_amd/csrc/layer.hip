@@ -252,7 +252,7 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
                                    const void* residual, int64_t ldres, void* y, int64_t ldy,
                                    const scmoe_routing_out* routing, void* workspace,
                                    size_t ws_bytes, void* stream_main, void* stream_aux) {
-  SCMOE_TRY(check_desc(D, 1, 1));
+  SCMOE_TRY(check_desc(D, 1, 2));
   SCMOE_TRY(check_weights(D, W, true));
   if (D->T == 0) return SCMOE_OK;
   if (!x_prev || !x_cur || !y || !workspace) return SCMOE_ERR_NULL;
@@ -291,7 +291,7 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
     hipError_t e = hipStreamWaitEvent(sm, ev->join, 0);
     if (e != hipSuccess) return hip_fail(e);
   }
-  SCMOE_TRY(combine(w.y_perm, D->d, D->dtype, w.dst_row, w.gate_w, D->T, D->d, 1, w.s, D->d, residual, ldres,
+  SCMOE_TRY(combine(w.y_perm, D->d, D->dtype, w.dst_row, w.gate_w, D->T, D->d, D->k, w.s, D->d, residual, ldres,
                     D->cg_mode != SCMOE_CG_NONE ? w.coef : nullptr, y, ldy, sm));
   return copy_routing(D, w, routing, sm);
 }

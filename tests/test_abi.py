@@ -104,7 +104,7 @@ def test_argument_errors_launch_nothing():
                                                       None, P, ws, None, None)
     assert call(desc, w, need - 1) == 4
     assert call(desc, B.Weights(P, None, P, None, P, None, None, None, P, None, None), need) == 1
-    assert call(B.make_desc(256, 64, 256, 4, 2, 80, B.F32), w, need) == 6
+    assert call(B.make_desc(256, 64, 256, 4, 3, 80, B.F32), w, need * 4) == 6
     assert call(B.make_desc(256, 64, 256, 4, 1, 80, B.F32, cg_mode=1), w, need * 2) == 1      # W_cg missing
     assert lib.moe_top2_layer_forward(C.byref(desc), P, 64, C.byref(w), P, 64, None, P, need, None) == 6
     assert lib.moe_topk_layer_forward(C.byref(desc), P, 64, C.byref(w), P, 64, None, P, 16, None) == 4

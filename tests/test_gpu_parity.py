@@ -258,6 +258,13 @@ def test_layer_bf16_mfma_path(oracle, k, shared, C_, normalize, cg, res, gelu):
         assert np.array_equal(y[dropped], s[dropped])
 
 
+def test_scmoe2_two_routed_experts_plus_shared(oracle):
+    """ScMoE-2: top-2 routing on x_prev with the shared expert on x_cur."""
+    L = inputs.make_layer(T=600, d=128, F=256, E=8, dtype="bf16", seed=51, biases=True, w_scale=0.05)
+    _layer_case(oracle, L, "bf16", 8, 2, 120, True, normalize=1)
+    _layer_case(oracle, L, "bf16", 8, 2, 100000, True, normalize=0, two_streams=True)
+
+
 def test_layer_f32_generic_path_with_options(oracle):
     L = inputs.make_layer(T=333, d=40, F=72, E=5, dtype="f32", seed=21, biases=True, cg_rows=1, w_scale=0.1)
     _layer_case(oracle, L, "f32", 5, 1, 50, True, cg_mode=1, residual=True)

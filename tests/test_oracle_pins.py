@@ -377,7 +377,8 @@ def _tiny(seed, T=48, d=12, F=20, E=4, biases=True, cg_rows=0, w_scale=0.3):
 @pytest.mark.parametrize("k,shared,C,normalize,cg,res", [
     (1, 1, 1000, 0, 0, False), (1, 1, 9, 0, 0, True), (2, 0, 1000, 1, 0, False),
     (2, 0, 14, 1, 0, False), (2, 0, 14, 0, 0, False), (1, 1, 9, 0, 1, False),
-    (1, 1, 1000, 0, 2, True), (1, 0, 9, 0, 0, False), (1, 1, 0, 0, 0, False)])
+    (1, 1, 1000, 0, 2, True), (1, 0, 9, 0, 0, False), (1, 1, 0, 0, 0, False),
+    (2, 1, 14, 1, 0, False), (2, 1, 1000, 0, 1, True)])
 def test_layer_bruteforce(oracle, k, shared, C, normalize, cg, res):
     L = _tiny(11 + k + C % 7, cg_rows=cg)
     E = L["Wg"].shape[1]
