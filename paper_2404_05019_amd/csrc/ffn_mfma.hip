@@ -28,6 +28,8 @@
 
 #include <stdlib.h>
 
+#include <type_traits>
+
 namespace scmoe {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -224,28 +226,36 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   // ---- fragment read offsets (the same for every tile) --------------------------------------
   const int wave_m = wave / CFG::WN, wave_n = wave % CFG::WN;
   const int lr = lane & 31, lh = lane >> 5;
-  int xoff[MI], woff[NJ];   // byte offset of (row, chunk lh) for k16-step 0, swizzled
+  // LDS byte address of (row, chunk lh) for k16-step 0 of stage 0, swizzled.  Kept as plain
+  // integers on top of an opaque base so that the address of any (stage, step, subtile) is
+  // one loop-invariant register plus an immediate: no address temporaries in the main loop
+  // that could alias fragment registers whose reads are still in flight.
+  unsigned lds0 = static_cast<unsigned>(reinterpret_cast<uintptr_t>(SCMOE_LDS_PTR(smem)));
+  asm volatile("" : "+s"(lds0));
+  unsigned xoff[MI], woff[NJ];
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     const int row = wave_m * CFG::TM + i * 32 + lr;
-    xoff[i] = row * RB + ((lh ^ swz<CPR>(row)) << 4);
+    xoff[i] = lds0 + row * RB + ((lh ^ swz<CPR>(row)) << 4);
   }
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int row = wave_n * CFG::TN + j * 32 + lr;
-    woff[j] = A_BYTES + row * RB + ((lh ^ swz<CPR>(row)) << 4);
+    woff[j] = lds0 + A_BYTES + row * RB + ((lh ^ swz<CPR>(row)) << 4);
   }
+  typedef const __attribute__((address_space(3))) bf16x8_t* lds_frag_ptr;
 
   f32x16_t acc[MI][NJ];
   bf16x8_t xf[2][MI], wf[2][NJ];
-  auto load_frags = [&](const unsigned char* st, int s, int buf) {
-    // k16-step s reads chunks 2s and 2s+1: an XOR on the swizzled chunk index
+  auto load_frags = [&](int st, int s, int buf) {   // st: byte offset of the stage
+    // k16-step s reads chunks 2s and 2s+1: an XOR on the swizzled chunk index.  Read order =
+    // order of first use by the MFMAs (row-subtile major), so that the counter waits before
+    // the MFMAs of the next step can be partial.
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
-      xf[buf][i] = *reinterpret_cast<const bf16x8_t*>(st + (xoff[i] ^ (s << 5)));
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-      wf[buf][j] = *reinterpret_cast<const bf16x8_t*>(st + (woff[j] ^ (s << 5)));
+    for (int t = 0; t < (MI > NJ ? MI : NJ); ++t) {
+      if (t < NJ) wf[buf][t] = *reinterpret_cast<lds_frag_ptr>(static_cast<uintptr_t>((woff[t] ^ (s << 5)) + st));
+      if (t < MI) xf[buf][t] = *reinterpret_cast<lds_frag_ptr>(static_cast<uintptr_t>((xoff[t] ^ (s << 5)) + st));
+    }
   };
   auto mfma_step = [&](int buf) {
 #pragma unroll
@@ -276,11 +286,14 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     if (first) wait_tiles((nk < NS ? nk : NS) - 1);
     else wait_tiles(0);
     __syncthreads();
-    load_frags(smem, 0, 0);
-    int stage = 0;                      // kt % NS
-    for (int kt = 0; kt < nk; ++kt) {
-      const unsigned char* st = smem + stage * STAGE;
-      const int next = (stage + 1 == NS) ? 0 : stage + 1;
+    load_frags(0, 0, 0);
+    // One k-tile with its LDS stage known at compile time (the k loop is unrolled NS-fold),
+    // so every LDS address is a loop-invariant register plus an immediate and no address
+    // arithmetic has to share registers with fragments that are still in flight.
+    auto k_tile = [&](auto stage_c, int kt) {
+      constexpr int stage = decltype(stage_c)::value;
+      constexpr int next = (stage + 1 == NS) ? 0 : stage + 1;
+      constexpr int st = stage * STAGE;
 #pragma unroll
       for (int s = 0; s + 1 < KS; ++s) {
         __builtin_amdgcn_sched_barrier(0);
@@ -303,11 +316,20 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
         wait_tiles(later < NS - 2 ? later : NS - 2);
         __syncthreads();
         if (kt + NS < nk) issue_loads(kt + NS, stage);
-        load_frags(smem + next * STAGE, 0, 0);
+        load_frags(next * STAGE, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
       mfma_step((KS - 1) & 1);
-      stage = next;
+    };
+    for (int kt = 0; kt < nk; kt += NS) {
+      k_tile(std::integral_constant<int, 0>{}, kt);
+      if (kt + 1 < nk) k_tile(std::integral_constant<int, 1>{}, kt + 1);
+      if constexpr (NS > 2) {
+        if (kt + 2 < nk) k_tile(std::integral_constant<int, 2>{}, kt + 2);
+      }
+      if constexpr (NS > 3) {
+        if (kt + 3 < nk) k_tile(std::integral_constant<int, 3>{}, kt + 3);
+      }
     }
 
     // ---- next tile: its first k-tiles are requested before this tile's epilogue -----------
