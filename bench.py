@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="1: all kernels in order on one stream; 2: shared expert on a second stream")
     ap.add_argument("--gemm-variant", type=int, default=None)
+    ap.add_argument("--padded-weights", action="store_true",
+                    help="store the expert weights with the padded row stride of scmoe_padded_ld "
+                         "instead of dense rows")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -76,7 +79,7 @@ def main():
     T, d, F, E, C_ = cfg["T"], cfg["d"], cfg["F"], cfg["E"], cfg["C"]
     dtype = cfg["dtype"]
     eb = 2 if dtype == "bf16" else 4
-    D = DevLayer(L, dtype)
+    D = DevLayer(L, dtype, pad_weights=args.padded_weights)
     t_gen = time.time() - t_gen
 
     desc = B.make_desc(T, d, F, E, 1, C_, D.code)
@@ -104,7 +107,7 @@ def main():
     counts, offsets, dst_row, src_token = i32(E), i32(E + 1), i32(T), i32(min(T, E * C_))
     rows = min(T, E * C_)
     x_perm = torch.empty((rows, d), dtype=D.tdtype, device=DEV)
-    hidden = torch.empty((rows, F), dtype=D.tdtype, device=DEV)
+    hidden = torch.empty((rows, B.scmoe_padded_ld(F, D.code)), dtype=D.tdtype, device=DEV)[:, :F]
     y_perm = torch.empty((rows, d), dtype=D.tdtype, device=DEV)
     s_out = torch.empty((T, d), dtype=D.tdtype, device=DEV)
     dws = torch.empty(max(B.scmoe_dispatch_workspace_bytes(T, E, 1), 16), dtype=torch.uint8, device=DEV)
@@ -190,7 +193,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if is_mfma else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "d_model": d, "d_ffn": F, "E": E, "top_k": 1,
-                   "capacity": C_, "kept_rows": K, "streams": args.streams},
+                   "capacity": C_, "kept_rows": K, "streams": args.streams,
+                   "weight_rows": "padded (scmoe_padded_ld)" if args.padded_weights else "dense"},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "ops": ops,
         "layer_tflops": round((4.0 * (K + T) * d * F) / (ms_per_step * 1e-3) / 1e12, 2),
         "input_generation_s": round(t_gen, 1),

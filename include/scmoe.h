@@ -92,6 +92,10 @@ typedef struct scmoe_weights {
   const void* W2s;   /* [d, F]                                                         */
   const float* b2s;  /* [d] or NULL                                                    */
   const float* W_cg; /* [1, d] (CG-1) or [2, d] (CG-2), fp32; NULL when cg_mode == 0   */
+  int64_t ld_w1;     /* row stride, in elements, of W1 and W1s (>= d; 0 means d).  Expert e
+                        of W1 starts at element e * F * ld_w1                          */
+  int64_t ld_w2;     /* row stride, in elements, of W2 and W2s (>= F; 0 means F).  Expert e
+                        of W2 starts at element e * d * ld_w2                          */
 } scmoe_weights;
 
 /* Optional copies of the routing state of a layer call.  Each member may be NULL. */
@@ -116,6 +120,16 @@ int scmoe_last_hip_error(void);
  * workgroups per CU).  Results agree to bf16 rounding of the same fp32 sums; only speed
  * differs.  Other values give SCMOE_ERR_ARG. */
 int scmoe_set_gemm_variant(int32_t variant);
+
+/* Row stride (in elements) that staggers the rows of a GEMM operand of `width` columns:
+ * `width` itself, or `width` plus 128 bytes of padding when the dense stride is a multiple
+ * of 512 bytes.  With every operand and the output at power-of-two strides, all workgroups
+ * reach the same cache channels in step; staggering any one of the matrices breaks that up
+ * (measured +19 % on a dense 32768 x 8192 x 2048 bf16 product with no bias).  The layer
+ * calls lay out their intermediate `hidden` this way, which is enough for them; the helper
+ * is for callers of scmoe_expert_ffn, who own `hidden`, and for weight strides if wanted.
+ * Host only; `ld` is a host pointer. */
+int scmoe_padded_ld(int32_t width, int32_t dtype, int64_t* ld);
 
 /* Capacity from a capacity factor (Tables 8-9 give only the factor): C = ceil(cf*k*T/E),
  * the ceiling taken after removing rounding noise of the double product.  Host only.
@@ -191,17 +205,20 @@ int scmoe_dispatch(const void* x, int64_t ldx, int32_t dtype, const int32_t* exp
  *
  * offsets: [E+1] on the DEVICE (read by the kernels, never by the host); offsets[E] must
  * not exceed max_rows, the number of rows x_perm / hidden / y_perm hold (rows past
- * offsets[E] are not touched).  W1: [E, F, d], W2: [E, d, F] in `dtype`; b1 [E, F],
- * b2 [E, d] fp32 or NULL.  hidden: caller scratch [max_rows, F] in `dtype`, row stride F.
+ * offsets[E] are not touched).  W1: [E, F, d] with row stride ldw1 (expert e starts at
+ * element e * F * ldw1), W2: [E, d, F] with row stride ldw2, in `dtype`; b1 [E, F],
+ * b2 [E, d] fp32 or NULL.  hidden: caller scratch [max_rows, F] in `dtype`, row stride ldh.
+ * All strides are in elements, multiples of 8, and at least the row width.
  * bf16: fp32 accumulation, hidden and y_perm rounded to bf16 (RNE) on store.
  * With E = 1 and offsets = {0, T} this is the dense MLP used for the shared expert
  * (Eq. (6)).
  */
 int scmoe_expert_ffn(const void* x_perm, int64_t ld_perm, int32_t dtype,
                      const int32_t* offsets, int32_t max_rows, int32_t E, int32_t d,
-                     int32_t F, const void* W1, const float* b1, const void* W2,
-                     const float* b2, void* hidden, void* y_perm, int64_t ldy,
-                     int32_t gelu_mode, void* stream);
+                     int32_t F, const void* W1, int64_t ldw1, const float* b1,
+                     const void* W2, int64_t ldw2, const float* b2, void* hidden,
+                     int64_t ldh, void* y_perm, int64_t ldy, int32_t gelu_mode,
+                     void* stream);
 
 /*
  * Output decode (Sec. 2.2) fused with the merge of Eq. (6)/(7):

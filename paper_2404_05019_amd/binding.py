@@ -17,7 +17,8 @@ GELU_ERF, GELU_TANH = 0, 1
 CG_NONE, CG_1, CG_2 = 0, 1, 2
 MAX_EXPERTS = 64
 
-EXPORTS = ["scmoe_status_string", "scmoe_last_hip_error", "scmoe_set_gemm_variant", "scmoe_capacity", "scmoe_gate_top1",
+EXPORTS = ["scmoe_status_string", "scmoe_last_hip_error", "scmoe_set_gemm_variant", "scmoe_padded_ld", "scmoe_capacity",
+           "scmoe_gate_top1",
            "scmoe_gate_top2", "scmoe_dispatch_workspace_bytes", "scmoe_dispatch", "scmoe_expert_ffn",
            "scmoe_combine", "scmoe_coef_gate", "scmoe_workspace_bytes", "scmoe_layer_forward",
            "moe_topk_layer_forward", "moe_top2_layer_forward"]
@@ -30,7 +31,8 @@ class Desc(C.Structure):
 
 class Weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
-                ("W_g", "bias", "W1", "b1", "W2", "b2", "W1s", "b1s", "W2s", "b2s", "W_cg")]
+                ("W_g", "bias", "W1", "b1", "W2", "b2", "W1s", "b1s", "W2s", "b2s", "W_cg")] + \
+               [("ld_w1", C.c_int64), ("ld_w2", C.c_int64)]
 
 
 class RoutingOut(C.Structure):
@@ -61,13 +63,14 @@ def lib():
         _lib.scmoe_status_string.argtypes = [C.c_int]
         i32, i64, vp, sz = C.c_int32, C.c_int64, C.c_void_p, C.c_size_t
         _lib.scmoe_capacity.argtypes = [i32, i32, i32, C.c_double, C.POINTER(i32)]
+        _lib.scmoe_padded_ld.argtypes = [i32, i32, C.POINTER(i64)]
         _lib.scmoe_gate_top1.argtypes = [vp, i64, i32, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
         _lib.scmoe_gate_top2.argtypes = _lib.scmoe_gate_top1.argtypes
         _lib.scmoe_dispatch_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
         _lib.scmoe_dispatch.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i64,
                                         vp, sz, vp]
-        _lib.scmoe_expert_ffn.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64,
-                                          i32, vp]
+        _lib.scmoe_expert_ffn.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, vp, i64, vp, vp, i64, vp, vp, i64,
+                                          vp, i64, i32, vp]
         _lib.scmoe_combine.argtypes = [vp, i64, i32, vp, vp, i32, i32, i32, vp, i64, vp, i64, vp, vp, i64, vp]
         _lib.scmoe_coef_gate.argtypes = [vp, i64, i32, vp, i32, i32, i32, vp, vp]
         _lib.scmoe_workspace_bytes.argtypes = [C.POINTER(Desc), C.POINTER(sz)]
@@ -104,6 +107,17 @@ def _ld(t):
     return t.stride(0)
 
 
+def _ldw(t):
+    """Row stride in elements of a weight tensor [E, out, in] or [out, in] whose rows are
+    contiguous and whose experts follow each other at out * stride."""
+    if t is None:
+        return 0
+    assert t.stride(-1) == 1, "rows must be contiguous"
+    ld = t.stride(-2)
+    assert t.dim() == 2 or t.shape[0] == 1 or t.stride(0) == t.shape[1] * ld, "experts must be evenly spaced"
+    return ld
+
+
 def _stream(s):
     if s is None:
         return torch.cuda.current_stream().cuda_stream
@@ -112,6 +126,12 @@ def _stream(s):
 
 def scmoe_set_gemm_variant(variant):
     _check(lib().scmoe_set_gemm_variant(int(variant)), "scmoe_set_gemm_variant")
+
+
+def scmoe_padded_ld(width, dtype):
+    out = C.c_int64(0)
+    _check(lib().scmoe_padded_ld(width, dtype, C.byref(out)), "scmoe_padded_ld")
+    return out.value
 
 
 def scmoe_capacity(T, E, k, cf):
@@ -156,8 +176,9 @@ def scmoe_expert_ffn(x_perm, offsets, max_rows, W1, b1, W2, b2, hidden, y_perm, 
                      stream=None):
     E, F, d = W1.shape
     _check(lib().scmoe_expert_ffn(_ptr(x_perm), _ld(x_perm), dtype_code(x_perm), _ptr(offsets), max_rows, E,
-                                  d, F, _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(hidden), _ptr(y_perm),
-                                  _ld(y_perm), gelu_mode, _stream(stream)), "scmoe_expert_ffn")
+                                  d, F, _ptr(W1), _ldw(W1), _ptr(b1), _ptr(W2), _ldw(W2), _ptr(b2), _ptr(hidden),
+                                  _ld(hidden), _ptr(y_perm), _ld(y_perm), gelu_mode, _stream(stream)),
+           "scmoe_expert_ffn")
 
 
 def scmoe_combine(y_perm, dst_row, gate_w, k, base, residual, coef, y, stream=None):
@@ -179,9 +200,14 @@ def make_desc(T, d, F, E, k, capacity, dtype, gelu_mode=GELU_ERF, normalize=0, c
 
 def make_weights(W_g, W1, W2, W1s=None, W2s=None, bias=None, b1=None, b2=None, b1s=None, b2s=None,
                  W_cg=None):
-    """Struct of device pointers.  The caller keeps the tensors alive."""
+    """Struct of device pointers.  The caller keeps the tensors alive.  W1 / W2 may be views
+    with padded rows (see scmoe_padded_ld); the shared expert's weights then use the same
+    row strides."""
+    ld1, ld2 = _ldw(W1), _ldw(W2)
+    assert W1s is None or _ldw(W1s) == ld1, "W1 and W1s must share one row stride"
+    assert W2s is None or _ldw(W2s) == ld2, "W2 and W2s must share one row stride"
     return Weights(_ptr(W_g), _ptr(bias), _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2), _ptr(W1s), _ptr(b1s),
-                   _ptr(W2s), _ptr(b2s), _ptr(W_cg))
+                   _ptr(W2s), _ptr(b2s), _ptr(W_cg), ld1, ld2)
 
 
 def make_routing_out(expert_idx=None, gate_w=None, counts=None, offsets=None, dst_row=None, src_token=None):

@@ -65,18 +65,32 @@ __device__ __forceinline__ float gelu_f32(float v, int mode) {
 }
 
 // ---- entry points implemented in one source and used by the layer orchestration --------
-int ffn_generic(const void* x, int64_t ldx, int dtype, const int32_t* offsets, int max_rows,
-                int E, int d, int F, const void* W1, const float* b1, const void* W2,
-                const float* b2, void* hidden, void* y, int64_t ldy, int gelu_mode,
-                hipStream_t stream);
+// One expert-FFN call over packed segments.  All strides in elements.
+struct FfnArgs {
+  const void* x; int64_t ldx;      // [rows, d] activations
+  const int32_t* gather;           // row r reads x[gather[r]] (the dispatch permutation applied
+                                   // on load); nullptr = identity.  MFMA path only.
+  const int32_t* offsets;          // [E + 1] segment starts, device
+  int max_rows, E, d, F;
+  const void* W1; int64_t ldw1; const float* b1;   // [E, F, d]
+  const void* W2; int64_t ldw2; const float* b2;   // [E, d, F]
+  void* hidden; int64_t ldh;       // [rows, F] scratch
+  void* y; int64_t ldy;            // [rows, d]
+  int gelu_mode;
+};
 
-// bf16 MFMA path.  `gather` (may be nullptr) holds, for every packed row, the row of x to
-// read (the dispatch permutation applied on load).  Returns SCMOE_ERR_ARG when the shape is
-// outside what the MFMA kernels cover (the caller then uses ffn_generic).
-int ffn_mfma_bf16(const void* x, int64_t ldx, const int32_t* gather, const int32_t* offsets,
-                  int max_rows, int E, int d, int F, const void* W1, const float* b1,
-                  const void* W2, const float* b2, void* hidden, void* y, int64_t ldy,
-                  int gelu_mode, hipStream_t stream);
+int ffn_generic(const FfnArgs& a, int dtype, hipStream_t stream);
+
+// bf16 MFMA path.  Returns SCMOE_ERR_ARG when the shape is outside what the MFMA kernels
+// cover (the caller then uses ffn_generic).
+int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream);
+
+// Row stride the grouped GEMM likes for an operand of `width` columns: rows at a multiple
+// of 512 bytes get 128 bytes of padding.
+inline int64_t padded_ld(int64_t width, int dtype) {
+  const int64_t eb = elem_bytes(dtype);
+  return ((width * eb) % 512 == 0) ? width + 128 / eb : width;
+}
 bool ffn_mfma_supported(int d, int F);
 
 }  // namespace scmoe

@@ -26,7 +26,7 @@ __device__ __forceinline__ void store_elem(unsigned char* p, int64_t i, float v)
 template <bool BF16, bool ACT>
 __global__ __launch_bounds__(256) void ffn_generic_kernel(
     const unsigned char* __restrict__ A, int64_t lda, const int32_t* __restrict__ offsets, int E,
-    int N, int Kd, const unsigned char* __restrict__ W, const float* __restrict__ bias,
+    int N, int Kd, const unsigned char* __restrict__ W, int64_t ldw, const float* __restrict__ bias,
     unsigned char* __restrict__ C, int64_t ldc, int gelu_mode) {
   __shared__ float As[GK][GT + 1];
   __shared__ float Bs[GK][GT + 1];
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(
   }
   if (!found) return;
   const int n0 = blockIdx.y * GT;
-  const unsigned char* We = W + static_cast<int64_t>(e) * N * Kd * (BF16 ? 2 : 4);
+  const unsigned char* We = W + static_cast<int64_t>(e) * N * ldw * (BF16 ? 2 : 4);
   const int tid = threadIdx.x;
   const int tx = tid & 15, ty = tid >> 4;
   float acc[4][4];
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(
       const int r = idx >> 4, kk = idx & 15;
       const int row = row0 + r, kg = k0 + kk, n = n0 + r;
       As[kk][r] = (row < row_end && kg < Kd) ? load_elem<BF16>(A, static_cast<int64_t>(row) * lda + kg) : 0.0f;
-      Bs[kk][r] = (n < N && kg < Kd) ? load_elem<BF16>(We, static_cast<int64_t>(n) * Kd + kg) : 0.0f;
+      Bs[kk][r] = (n < N && kg < Kd) ? load_elem<BF16>(We, static_cast<int64_t>(n) * ldw + kg) : 0.0f;
     }
     __syncthreads();
 #pragma unroll
@@ -95,27 +95,25 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(
   }
 }
 
-int ffn_generic(const void* x, int64_t ldx, int dtype, const int32_t* offsets, int max_rows, int E,
-                int d, int F, const void* W1, const float* b1, const void* W2, const float* b2,
-                void* hidden, void* y, int64_t ldy, int gelu_mode, hipStream_t stream) {
-  const int mt = (max_rows + GT - 1) / GT + E;  // upper bound on row tiles over all segments
-  const unsigned char* xb = static_cast<const unsigned char*>(x);
-  const unsigned char* w1 = static_cast<const unsigned char*>(W1);
-  const unsigned char* w2 = static_cast<const unsigned char*>(W2);
-  unsigned char* hb = static_cast<unsigned char*>(hidden);
-  unsigned char* yb = static_cast<unsigned char*>(y);
+int ffn_generic(const FfnArgs& a, int dtype, hipStream_t stream) {
+  const int mt = (a.max_rows + GT - 1) / GT + a.E;  // upper bound on row tiles over all segments
+  const unsigned char* xb = static_cast<const unsigned char*>(a.x);
+  const unsigned char* w1 = static_cast<const unsigned char*>(a.W1);
+  const unsigned char* w2 = static_cast<const unsigned char*>(a.W2);
+  unsigned char* hb = static_cast<unsigned char*>(a.hidden);
+  unsigned char* yb = static_cast<unsigned char*>(a.y);
   dim3 block(256);
-  dim3 g1(mt, (F + GT - 1) / GT), g2(mt, (d + GT - 1) / GT);
+  dim3 g1(mt, (a.F + GT - 1) / GT), g2(mt, (a.d + GT - 1) / GT);
   if (dtype == SCMOE_BF16) {
-    hipLaunchKernelGGL((ffn_generic_kernel<true, true>), g1, block, 0, stream, xb, ldx, offsets, E, F, d, w1, b1,
-                       hb, static_cast<int64_t>(F), gelu_mode);
-    hipLaunchKernelGGL((ffn_generic_kernel<true, false>), g2, block, 0, stream, hb, static_cast<int64_t>(F),
-                       offsets, E, d, F, w2, b2, yb, ldy, gelu_mode);
+    hipLaunchKernelGGL((ffn_generic_kernel<true, true>), g1, block, 0, stream, xb, a.ldx, a.offsets, a.E, a.F,
+                       a.d, w1, a.ldw1, a.b1, hb, a.ldh, a.gelu_mode);
+    hipLaunchKernelGGL((ffn_generic_kernel<true, false>), g2, block, 0, stream, hb, a.ldh, a.offsets, a.E, a.d,
+                       a.F, w2, a.ldw2, a.b2, yb, a.ldy, a.gelu_mode);
   } else {
-    hipLaunchKernelGGL((ffn_generic_kernel<false, true>), g1, block, 0, stream, xb, ldx, offsets, E, F, d, w1, b1,
-                       hb, static_cast<int64_t>(F), gelu_mode);
-    hipLaunchKernelGGL((ffn_generic_kernel<false, false>), g2, block, 0, stream, hb, static_cast<int64_t>(F),
-                       offsets, E, d, F, w2, b2, yb, ldy, gelu_mode);
+    hipLaunchKernelGGL((ffn_generic_kernel<false, true>), g1, block, 0, stream, xb, a.ldx, a.offsets, a.E, a.F,
+                       a.d, w1, a.ldw1, a.b1, hb, a.ldh, a.gelu_mode);
+    hipLaunchKernelGGL((ffn_generic_kernel<false, false>), g2, block, 0, stream, hb, a.ldh, a.offsets, a.E, a.d,
+                       a.F, w2, a.ldw2, a.b2, yb, a.ldy, a.gelu_mode);
   }
   return launch_status();
 }

@@ -217,10 +217,15 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   };
   // wait until at most `tiles` of the newest k-tiles are still in flight (loads complete in
   // issue order, LPW loads per k-tile and wave)
+  auto wait_vm = [&](auto n_c) {
+    constexpr int n = decltype(n_c)::value;
+    static_assert(n < 64, "vmcnt field");
+    __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | 0x0F70);
+  };
   auto wait_tiles = [&](int tiles) {
-    if (tiles >= 2) __builtin_amdgcn_s_waitcnt(((2 * LPW) & 15) | (((2 * LPW) >> 4) << 14) | 0x0F70);
-    else if (tiles == 1) __builtin_amdgcn_s_waitcnt((LPW & 15) | ((LPW >> 4) << 14) | 0x0F70);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (tiles >= 2) wait_vm(std::integral_constant<int, 2 * LPW>{});
+    else if (tiles == 1) wait_vm(std::integral_constant<int, LPW>{});
+    else wait_vm(std::integral_constant<int, 0>{});
   };
 
   // ---- fragment read offsets (the same for every tile) --------------------------------------
@@ -269,7 +274,6 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   locate(L, e, row0, row_end, n0);
   set_ptrs(e, row0, row_end, n0);
   issue_prologue();
-  bool first = true;
   for (;;) {
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -283,52 +287,77 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     // ds_read slotted behind an MFMA; one workgroup barrier per k-tile.  After an epilogue
     // the stores of the previous tile share the counter with the loads, so everything is
     // waited for (the prologue loads had the whole epilogue to land).
-    if (first) wait_tiles((nk < NS ? nk : NS) - 1);
-    else wait_tiles(0);
+    wait_vm(std::integral_constant<int, 0>{});
     __syncthreads();
     load_frags(0, 0, 0);
     // One k-tile with its LDS stage known at compile time (the k loop is unrolled NS-fold),
     // so every LDS address is a loop-invariant register plus an immediate and no address
     // arithmetic has to share registers with fragments that are still in flight.
-    auto k_tile = [&](auto stage_c, int kt) {
+    auto k_tile = [&](auto stage_c, auto steady_c, int kt) {
       constexpr int stage = decltype(stage_c)::value;
+      constexpr bool steady = decltype(steady_c)::value;   // k-tiles kt+1 .. kt+NS all exist
       constexpr int next = (stage + 1 == NS) ? 0 : stage + 1;
       constexpr int st = stage * STAGE;
-#pragma unroll
-      for (int s = 0; s + 1 < KS; ++s) {
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(st, s + 1, (s + 1) & 1);
-        mfma_step(s & 1);
-        // issue order: MFMA, ds_read, MFMA, ds_read, ... (the reads feed the NEXT step)
+      // issue order of one step: MFMA, ds_read, MFMA, ds_read, ... (the reads feed the NEXT step)
+      auto interleave = [&]() {
 #pragma unroll
         for (int q = 0; q < MI + NJ; ++q) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, MI * NJ - (MI + NJ), 0);
+      };
+#pragma unroll
+      for (int s = 0; s + 1 < KS; ++s) {
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(st, s + 1, (s + 1) & 1);
+        mfma_step(s & 1);
+        interleave();
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (kt + 1 < nk) {
-        // k-tiles kt+1 .. min(kt+NS-1, nk-1) are in flight; k-tile kt+1 must have landed.
-        // After the barrier it has for every wave, and every wave holds its last fragments
-        // of k-tile kt in registers, so this stage can be refilled with k-tile kt+NS.
-        const int later = nk - kt - 2;
-        wait_tiles(later < NS - 2 ? later : NS - 2);
+      if constexpr (steady) {
+        // No branches here: the compiler's counter bookkeeping merges conservatively at every
+        // join, and a full LDS wait ahead of the last step would idle the MFMA pipe while all
+        // waves fetch the next stage's first fragments at once.
+        wait_tiles(NS - 2);
         __syncthreads();
-        if (kt + NS < nk) issue_loads(kt + NS, stage);
+        issue_loads(kt + NS, stage);
+        __builtin_amdgcn_sched_barrier(0);
         load_frags(next * STAGE, 0, 0);
+        mfma_step((KS - 1) & 1);
+        interleave();
+      } else {
+        if (kt + 1 < nk) {
+          // k-tiles kt+1 .. min(kt+NS-1, nk-1) are in flight; k-tile kt+1 must have landed.
+          // After the barrier it has for every wave, and every wave holds its last fragments
+          // of k-tile kt in registers, so this stage can be refilled with k-tile kt+NS.
+          const int later = nk - kt - 2;
+          wait_tiles(later < NS - 2 ? later : NS - 2);
+          __syncthreads();
+          if (kt + NS < nk) issue_loads(kt + NS, stage);
+          load_frags(next * STAGE, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step((KS - 1) & 1);
       }
-      __builtin_amdgcn_sched_barrier(0);
-      mfma_step((KS - 1) & 1);
     };
-    for (int kt = 0; kt < nk; kt += NS) {
-      k_tile(std::integral_constant<int, 0>{}, kt);
-      if (kt + 1 < nk) k_tile(std::integral_constant<int, 1>{}, kt + 1);
+    using std::integral_constant;
+    using std::bool_constant;
+    int kt = 0;
+    for (; kt + 2 * NS <= nk; kt += NS) {       // steady state: every load and read exists
+      k_tile(integral_constant<int, 0>{}, bool_constant<true>{}, kt);
+      k_tile(integral_constant<int, 1>{}, bool_constant<true>{}, kt + 1);
+      if constexpr (NS > 2) k_tile(integral_constant<int, 2>{}, bool_constant<true>{}, kt + 2);
+      if constexpr (NS > 3) k_tile(integral_constant<int, 3>{}, bool_constant<true>{}, kt + 3);
+    }
+    for (; kt < nk; kt += NS) {                 // the last k-tiles (fewer than 2 NS), guarded
+      k_tile(integral_constant<int, 0>{}, bool_constant<false>{}, kt);
+      if (kt + 1 < nk) k_tile(integral_constant<int, 1>{}, bool_constant<false>{}, kt + 1);
       if constexpr (NS > 2) {
-        if (kt + 2 < nk) k_tile(std::integral_constant<int, 2>{}, kt + 2);
+        if (kt + 2 < nk) k_tile(integral_constant<int, 2>{}, bool_constant<false>{}, kt + 2);
       }
       if constexpr (NS > 3) {
-        if (kt + 3 < nk) k_tile(std::integral_constant<int, 3>{}, kt + 3);
+        if (kt + 3 < nk) k_tile(integral_constant<int, 3>{}, bool_constant<false>{}, kt + 3);
       }
     }
 
@@ -396,7 +425,6 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     }
     if (!more) break;
     L = Ln;
-    first = false;
   }
 }
 
@@ -469,43 +497,40 @@ static int launch_variant(const GemmArgs& a, int max_rows, hipStream_t stream) {
   }
 }
 
-int ffn_mfma_bf16(const void* x, int64_t ldx, const int32_t* gather, const int32_t* offsets,
-                  int max_rows, int E, int d, int F, const void* W1, const float* b1, const void* W2,
-                  const float* b2, void* hidden, void* y, int64_t ldy, int gelu_mode,
-                  hipStream_t stream) {
-  if (!ffn_mfma_supported(d, F)) return SCMOE_ERR_ARG;
-  if (max_rows <= 0) return SCMOE_OK;
+int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
+  if (!ffn_mfma_supported(a.d, a.F)) return SCMOE_ERR_ARG;
+  if (a.max_rows <= 0) return SCMOE_OK;
   GemmArgs g1{};
-  g1.A = static_cast<const unsigned char*>(x);
-  g1.lda = ldx;
-  g1.gather = gather;
-  g1.offsets = offsets;
-  g1.W = static_cast<const unsigned char*>(W1);
-  g1.ldw = d;
-  g1.bias = b1;
-  g1.C = static_cast<unsigned char*>(hidden);
-  g1.ldc = F;
-  g1.E = E;
-  g1.N = F;
-  g1.Kd = d;
-  g1.gelu_mode = gelu_mode;
-  int st = launch_variant<true>(g1, max_rows, stream);
+  g1.A = static_cast<const unsigned char*>(a.x);
+  g1.lda = a.ldx;
+  g1.gather = a.gather;
+  g1.offsets = a.offsets;
+  g1.W = static_cast<const unsigned char*>(a.W1);
+  g1.ldw = a.ldw1;
+  g1.bias = a.b1;
+  g1.C = static_cast<unsigned char*>(a.hidden);
+  g1.ldc = a.ldh;
+  g1.E = a.E;
+  g1.N = a.F;
+  g1.Kd = a.d;
+  g1.gelu_mode = a.gelu_mode;
+  int st = launch_variant<true>(g1, a.max_rows, stream);
   if (st != SCMOE_OK) return st;
   GemmArgs g2{};
-  g2.A = static_cast<const unsigned char*>(hidden);
-  g2.lda = F;
+  g2.A = static_cast<const unsigned char*>(a.hidden);
+  g2.lda = a.ldh;
   g2.gather = nullptr;
-  g2.offsets = offsets;
-  g2.W = static_cast<const unsigned char*>(W2);
-  g2.ldw = F;
-  g2.bias = b2;
-  g2.C = static_cast<unsigned char*>(y);
-  g2.ldc = ldy;
-  g2.E = E;
-  g2.N = d;
-  g2.Kd = F;
-  g2.gelu_mode = gelu_mode;
-  return launch_variant<false>(g2, max_rows, stream);
+  g2.offsets = a.offsets;
+  g2.W = static_cast<const unsigned char*>(a.W2);
+  g2.ldw = a.ldw2;
+  g2.bias = a.b2;
+  g2.C = static_cast<unsigned char*>(a.y);
+  g2.ldc = a.ldy;
+  g2.E = a.E;
+  g2.N = a.d;
+  g2.Kd = a.F;
+  g2.gelu_mode = a.gelu_mode;
+  return launch_variant<false>(g2, a.max_rows, stream);
 }
 
 }  // namespace scmoe

@@ -52,6 +52,7 @@ struct LayerWs {
   int32_t* expert_idx; float* gate_w; int32_t* counts; int32_t* offsets; int32_t* dst_row;
   int32_t* src_token; int32_t* offsets_shared; float* coef; void* disp_ws; size_t disp_bytes;
   void* x_perm; void* hidden; void* y_perm; void* hidden_s; void* s;
+  int64_t ldh;   // row stride of hidden and hidden_s
   size_t total;
 };
 
@@ -78,10 +79,11 @@ static LayerWs carve(const scmoe_desc* D, void* base, bool shared) {
   w.disp_bytes = dispatch_ws_bytes(D->T, D->E, D->k);
   w.disp_ws = take(w.disp_bytes);
   w.x_perm = take(rows * D->d * eb);
-  w.hidden = take(rows * D->F * eb);
+  w.ldh = padded_ld(D->F, D->dtype);
+  w.hidden = take(rows * w.ldh * eb);
   w.y_perm = take(rows * D->d * eb);
   if (shared) {
-    w.hidden_s = take(static_cast<size_t>(D->T) * D->F * eb);
+    w.hidden_s = take(static_cast<size_t>(D->T) * w.ldh * eb);
     w.s = take(static_cast<size_t>(D->T) * D->d * eb);
   }
   w.total = off;
@@ -96,18 +98,14 @@ __global__ void set_pair(int32_t* p, int a, int b) {
 }
 
 // FFN over segments: MFMA path for bf16 shapes it covers, else the generic kernel.
-static int expert_ffn_any(const void* x, int64_t ldx, int dtype, const int32_t* gather,
-                          const int32_t* offsets, int max_rows, int E, int d, int F, const void* W1,
-                          const float* b1, const void* W2, const float* b2, void* hidden, void* y,
-                          int64_t ldy, int gelu_mode, hipStream_t stream) {
-  if (max_rows <= 0) return SCMOE_OK;
-  if (dtype == SCMOE_BF16 && ffn_mfma_supported(d, F))
-    return ffn_mfma_bf16(x, ldx, gather, offsets, max_rows, E, d, F, W1, b1, W2, b2, hidden, y, ldy,
-                         gelu_mode, stream);
-  if (gather != nullptr) return SCMOE_ERR_ARG;  // the generic kernel reads packed rows only
-  return ffn_generic(x, ldx, dtype, offsets, max_rows, E, d, F, W1, b1, W2, b2, hidden, y, ldy,
-                     gelu_mode, stream);
+static int expert_ffn_any(const FfnArgs& a, int dtype, hipStream_t stream) {
+  if (a.max_rows <= 0) return SCMOE_OK;
+  if (dtype == SCMOE_BF16 && ffn_mfma_supported(a.d, a.F)) return ffn_mfma_bf16(a, stream);
+  if (a.gather != nullptr) return SCMOE_ERR_ARG;  // the generic kernel reads packed rows only
+  return ffn_generic(a, dtype, stream);
 }
+
+static inline int64_t ld_or(int64_t ld, int64_t dense) { return ld ? ld : dense; }
 
 static bool gather_on_load(const scmoe_desc* D) {
   return D->dtype == SCMOE_BF16 && ffn_mfma_supported(D->d, D->F);
@@ -168,11 +166,18 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
                      w.offsets, w.dst_row, w.src_token, gol ? nullptr : w.x_perm, D->d, w.disp_ws,
                      w.disp_bytes, stream));
   const int rows = static_cast<int>(packed_rows(D->T, D->E, D->k, D->capacity));
-  if (gol)
-    return expert_ffn_any(x, ldx, D->dtype, w.src_token, w.offsets, rows, D->E, D->d, D->F, W->W1, W->b1,
-                          W->W2, W->b2, w.hidden, w.y_perm, D->d, D->gelu_mode, stream);
-  return expert_ffn_any(w.x_perm, D->d, D->dtype, nullptr, w.offsets, rows, D->E, D->d, D->F, W->W1,
-                        W->b1, W->W2, W->b2, w.hidden, w.y_perm, D->d, D->gelu_mode, stream);
+  FfnArgs a{};
+  a.x = gol ? x : w.x_perm;
+  a.ldx = gol ? ldx : D->d;
+  a.gather = gol ? w.src_token : nullptr;
+  a.offsets = w.offsets;
+  a.max_rows = rows; a.E = D->E; a.d = D->d; a.F = D->F;
+  a.W1 = W->W1; a.ldw1 = ld_or(W->ld_w1, D->d); a.b1 = W->b1;
+  a.W2 = W->W2; a.ldw2 = ld_or(W->ld_w2, D->F); a.b2 = W->b2;
+  a.hidden = w.hidden; a.ldh = w.ldh;
+  a.y = w.y_perm; a.ldy = D->d;
+  a.gelu_mode = D->gelu_mode;
+  return expert_ffn_any(a, D->dtype, stream);
 }
 
 }  // namespace scmoe
@@ -197,6 +202,14 @@ extern "C" int scmoe_last_hip_error(void) { return g_last_hip_error; }
 namespace scmoe { int set_gemm_variant(int v); }
 extern "C" int scmoe_set_gemm_variant(int32_t variant) { return scmoe::set_gemm_variant(variant); }
 
+extern "C" int scmoe_padded_ld(int32_t width, int32_t dtype, int64_t* ld) {
+  if (!ld) return SCMOE_ERR_NULL;
+  if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
+  if (width <= 0) return SCMOE_ERR_SHAPE;
+  *ld = padded_ld(width, dtype);
+  return SCMOE_OK;
+}
+
 extern "C" int scmoe_capacity(int32_t T, int32_t E, int32_t k, double cf, int32_t* C) {
   if (!C) return SCMOE_ERR_NULL;
   if (T < 0 || E < 1 || k < 1 || !(cf >= 0.0)) return SCMOE_ERR_SHAPE;
@@ -211,20 +224,25 @@ extern "C" int scmoe_capacity(int32_t T, int32_t E, int32_t k, double cf, int32_
 
 extern "C" int scmoe_expert_ffn(const void* x_perm, int64_t ld_perm, int32_t dtype,
                                 const int32_t* offsets, int32_t max_rows, int32_t E, int32_t d,
-                                int32_t F, const void* W1, const float* b1, const void* W2,
-                                const float* b2, void* hidden, void* y_perm, int64_t ldy,
-                                int32_t gelu_mode, void* stream) {
+                                int32_t F, const void* W1, int64_t ldw1, const float* b1,
+                                const void* W2, int64_t ldw2, const float* b2, void* hidden,
+                                int64_t ldh, void* y_perm, int64_t ldy, int32_t gelu_mode,
+                                void* stream) {
   if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
   if (max_rows < 0 || E < 1 || d <= 0 || F <= 0 || (d % 8) || (F % 8)) return SCMOE_ERR_SHAPE;
   if (gelu_mode != SCMOE_GELU_ERF && gelu_mode != SCMOE_GELU_TANH) return SCMOE_ERR_ARG;
   if (max_rows == 0) return SCMOE_OK;
   if (!x_perm || !offsets || !W1 || !W2 || !hidden || !y_perm) return SCMOE_ERR_NULL;
-  if (!view_ok(x_perm, ld_perm, d, dtype) || !view_ok(y_perm, ldy, d, dtype) || !aligned16(hidden) ||
-      !aligned16(W1) || !aligned16(W2))
+  if (!view_ok(x_perm, ld_perm, d, dtype) || !view_ok(y_perm, ldy, d, dtype) || !view_ok(hidden, ldh, F, dtype) ||
+      !view_ok(W1, ldw1, d, dtype) || !view_ok(W2, ldw2, F, dtype))
     return SCMOE_ERR_SHAPE;
   if ((b1 && !aligned16(b1)) || (b2 && !aligned16(b2))) return SCMOE_ERR_SHAPE;
-  return expert_ffn_any(x_perm, ld_perm, dtype, nullptr, offsets, max_rows, E, d, F, W1, b1, W2, b2,
-                        hidden, y_perm, ldy, gelu_mode, static_cast<hipStream_t>(stream));
+  FfnArgs a{};
+  a.x = x_perm; a.ldx = ld_perm; a.gather = nullptr; a.offsets = offsets;
+  a.max_rows = max_rows; a.E = E; a.d = d; a.F = F;
+  a.W1 = W1; a.ldw1 = ldw1; a.b1 = b1; a.W2 = W2; a.ldw2 = ldw2; a.b2 = b2;
+  a.hidden = hidden; a.ldh = ldh; a.y = y_perm; a.ldy = ldy; a.gelu_mode = gelu_mode;
+  return expert_ffn_any(a, dtype, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out) {
@@ -244,6 +262,9 @@ static int check_weights(const scmoe_desc* D, const scmoe_weights* W, bool share
                         shared ? W->W2s : nullptr, shared ? W->b1s : nullptr, shared ? W->b2s : nullptr};
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return SCMOE_ERR_SHAPE;
+  const int v = vec_elems(D->dtype);
+  if (W->ld_w1 && (W->ld_w1 < D->d || W->ld_w1 % v)) return SCMOE_ERR_SHAPE;
+  if (W->ld_w2 && (W->ld_w2 < D->F || W->ld_w2 % v)) return SCMOE_ERR_SHAPE;
   return SCMOE_OK;
 }
 
@@ -277,8 +298,13 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   // shared expert on the current-layer representation (Eq. (6)/(7)): independent of routing
   hipLaunchKernelGGL(set_pair, dim3(1), dim3(64), 0, s_shared, w.offsets_shared, 0, D->T);
   SCMOE_TRY(launch_status());
-  SCMOE_TRY(expert_ffn_any(x_cur, ld_cur, D->dtype, nullptr, w.offsets_shared, D->T, 1, D->d, D->F, W->W1s,
-                           W->b1s, W->W2s, W->b2s, w.hidden_s, w.s, D->d, D->gelu_mode, s_shared));
+  FfnArgs se{};
+  se.x = x_cur; se.ldx = ld_cur; se.gather = nullptr; se.offsets = w.offsets_shared;
+  se.max_rows = D->T; se.E = 1; se.d = D->d; se.F = D->F;
+  se.W1 = W->W1s; se.ldw1 = ld_or(W->ld_w1, D->d); se.b1 = W->b1s;
+  se.W2 = W->W2s; se.ldw2 = ld_or(W->ld_w2, D->F); se.b2 = W->b2s;
+  se.hidden = w.hidden_s; se.ldh = w.ldh; se.y = w.s; se.ldy = D->d; se.gelu_mode = D->gelu_mode;
+  SCMOE_TRY(expert_ffn_any(se, D->dtype, s_shared));
   if (D->cg_mode != SCMOE_CG_NONE)
     SCMOE_TRY(coef_gate(x_cur, ld_cur, D->dtype, W->W_cg, D->cg_mode, D->T, D->d, w.coef, s_shared));
   if (two) {

@@ -8,15 +8,23 @@ from paper_2404_05019_amd import inputs
 DEV = "cuda:0"
 
 
-def to_dev(a, dtype):
-    """float32 numpy array whose values are representable in `dtype` -> device tensor."""
+def to_dev(a, dtype, ld=None):
+    """float32 numpy array whose values are representable in `dtype` -> device tensor.  With
+    `ld` the rows (last axis) are stored `ld` elements apart and the result is a view of the
+    padded storage; the padding holds a huge value, so that a kernel that reads it is caught."""
     if a is None:
         return None
     a = np.ascontiguousarray(a, dtype=np.float32)
     if dtype == "bf16":
         bits = inputs.bf16_bits(a)
-        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(DEV)
-    return torch.from_numpy(a).to(DEV)
+        t = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(DEV)
+    else:
+        t = torch.from_numpy(a).to(DEV)
+    if ld is None or ld == a.shape[-1]:
+        return t
+    store = torch.full(a.shape[:-1] + (ld,), 3.0e38, dtype=t.dtype, device=DEV)
+    store[..., :a.shape[-1]] = t
+    return store[..., :a.shape[-1]]
 
 
 def to_host(t):
@@ -37,20 +45,24 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 class DevLayer:
     """Device copies of a layer dict from inputs.make_layer, plus the weights struct."""
 
-    def __init__(self, L, dtype):
+    def __init__(self, L, dtype, pad_weights=False):
         self.dtype = dtype
+        self.code = B.BF16 if dtype == "bf16" else B.F32
         act = lambda k: to_dev(L.get(k), dtype)
+        # expert weights, optionally with the padded row stride the library recommends
+        wgt = lambda k: to_dev(L.get(k), dtype,
+                               B.scmoe_padded_ld(L[k].shape[-1], self.code) if pad_weights and L.get(k) is not None
+                               else None)
         f32 = lambda k: to_dev(L.get(k), "f32")
         self.x_prev, self.x_cur = act("x_prev"), act("x_cur")
         self.Wg, self.bias = f32("Wg"), f32("bias")
-        self.W1, self.W2, self.W1s, self.W2s = act("W1"), act("W2"), act("W1s"), act("W2s")
+        self.W1, self.W2, self.W1s, self.W2s = wgt("W1"), wgt("W2"), wgt("W1s"), wgt("W2s")
         self.b1, self.b2, self.b1s, self.b2s = f32("b1"), f32("b2"), f32("b1s"), f32("b2s")
         self.Wcg = f32("Wcg")
         self.weights = B.make_weights(self.Wg, self.W1, self.W2, self.W1s, self.W2s, self.bias, self.b1,
                                       self.b2, self.b1s, self.b2s, self.Wcg)
         self.E, self.F, self.d = self.W1.shape
         self.T = self.x_cur.shape[0]
-        self.code = B.BF16 if dtype == "bf16" else B.F32
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
 
 

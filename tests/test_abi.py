@@ -47,6 +47,16 @@ def test_capacity_host_function():
     assert B.lib().scmoe_capacity(1, 1, 1, 1.0, None) == 1
 
 
+def test_padded_ld_host_function():
+    assert B.scmoe_padded_ld(2048, B.BF16) == 2112 and B.scmoe_padded_ld(8192, B.BF16) == 8256
+    assert B.scmoe_padded_ld(384, B.BF16) == 384 and B.scmoe_padded_ld(64, B.F32) == 64
+    assert B.scmoe_padded_ld(128, B.F32) == 160
+    out = C.c_int64(0)
+    assert B.lib().scmoe_padded_ld(0, B.BF16, C.byref(out)) == 2
+    assert B.lib().scmoe_padded_ld(64, 7, C.byref(out)) == 3
+    assert B.lib().scmoe_padded_ld(64, B.BF16, None) == 1
+
+
 def test_workspace_sizes_and_desc_checks():
     d = B.make_desc(256, 64, 256, 4, 1, 80, B.F32)
     n = B.scmoe_workspace_bytes(d)
@@ -85,11 +95,15 @@ def test_argument_errors_launch_nothing():
     assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 3, 100, P, P, P, P, P, 64, P, 1 << 20, None) == 6
     assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 1, 100, None, P, P, P, P, 64, P, 1 << 20, None) == 1
     assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 1, -1, P, P, P, P, P, 64, P, 1 << 20, None) == 2
-    # expert ffn
-    assert lib.scmoe_expert_ffn(P, 64, B.BF16, P, 100, 2, 64, 100, P, None, P, None, P, P, 64, 0, None) == 2
-    assert lib.scmoe_expert_ffn(P, 64, B.BF16, None, 100, 2, 64, 128, P, None, P, None, P, P, 64, 0, None) == 1
-    assert lib.scmoe_expert_ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, None, P, None, P, P, 64, 4, None) == 6
-    assert lib.scmoe_expert_ffn(None, 64, B.BF16, None, 0, 2, 64, 128, None, None, None, None, None, None, 64, 0, None) == 0
+    # expert ffn: (x, ld, dtype, offsets, max_rows, E, d, F, W1, ldw1, b1, W2, ldw2, b2, hidden, ldh, y, ldy, gelu, stream)
+    ffn = lib.scmoe_expert_ffn
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 100, P, 64, None, P, 100, None, P, 100, P, 64, 0, None) == 2   # F % 8
+    assert ffn(P, 64, B.BF16, None, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 128, P, 64, 0, None) == 1
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 128, P, 64, 4, None) == 6
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 56, None, P, 128, None, P, 128, P, 64, 0, None) == 2   # ldw1 < d
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 132, None, P, 128, P, 64, 0, None) == 2   # ldw2 % 8
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 120, P, 64, 0, None) == 2   # ldh < F
+    assert ffn(None, 64, B.BF16, None, 0, 2, 64, 128, None, 64, None, None, 128, None, None, 128, None, 64, 0, None) == 0
     # combine / coefficient gate
     assert lib.scmoe_combine(P, 64, B.F32, P, P, 10, 64, 3, None, 0, None, 0, None, P, 64, None) == 6
     assert lib.scmoe_combine(P, 64, B.F32, None, P, 10, 64, 1, None, 0, None, 0, None, P, 64, None) == 1
@@ -98,12 +112,14 @@ def test_argument_errors_launch_nothing():
     assert lib.scmoe_coef_gate(P, 64, B.F32, None, 1, 10, 64, P, None) == 1
     # layer: short workspace, missing shared weights, k = 2 refused by the ScMoE entry
     desc = B.make_desc(256, 64, 256, 4, 1, 80, B.F32)
-    w = B.Weights(P, None, P, None, P, None, P, None, P, None, None)
+    w = B.Weights(P, None, P, None, P, None, P, None, P, None, None, 0, 0)
     need = B.scmoe_workspace_bytes(desc)
     call = lambda d_, w_, ws: lib.scmoe_layer_forward(C.byref(d_), P, 64, P, 64, C.byref(w_), None, 0, P, 64,
                                                       None, P, ws, None, None)
     assert call(desc, w, need - 1) == 4
-    assert call(desc, B.Weights(P, None, P, None, P, None, None, None, P, None, None), need) == 1
+    assert call(desc, B.Weights(P, None, P, None, P, None, None, None, P, None, None, 0, 0), need) == 1
+    assert call(desc, B.Weights(P, None, P, None, P, None, P, None, P, None, None, 60, 0), need) == 2     # ld_w1 < d
+    assert call(desc, B.Weights(P, None, P, None, P, None, P, None, P, None, None, 0, 258), need) == 2    # ld_w2 % 4
     assert call(B.make_desc(256, 64, 256, 4, 3, 80, B.F32), w, need * 4) == 6
     assert call(B.make_desc(256, 64, 256, 4, 1, 80, B.F32, cg_mode=1), w, need * 2) == 1      # W_cg missing
     assert lib.moe_top2_layer_forward(C.byref(desc), P, 64, C.byref(w), P, 64, None, P, need, None) == 6

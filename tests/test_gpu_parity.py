@@ -132,7 +132,7 @@ def test_dispatch_all_to_one_and_invalid(oracle):
 
 # ------------------------------------------------------------------------------- expert FFN
 
-def _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode, extra_rows=5, w_scale=0.05):
+def _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode, extra_rows=5, w_scale=0.05, pad=False):
     rng = np.random.default_rng(E * 100 + d + F)
     K = int(sum(lens))
     rows = K + extra_rows
@@ -144,10 +144,13 @@ def _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode, extra_rows=5, w_s
     b2 = (0.1 * rng.standard_normal((E, d))).astype(np.float32) if biases else None
     ref = oracle.expert_ffn(x, offsets, W1, W2, b1, b2, gelu_mode=gelu_mode)
     gx = to_dev(x, dtype)
-    hidden = torch.zeros((rows, F), dtype=gx.dtype, device=DEV)
+    code = B.BF16 if dtype == "bf16" else B.F32
+    # pad: weights and the hidden scratch at the row strides the library recommends
+    ld1, ld2 = (B.scmoe_padded_ld(d, code), B.scmoe_padded_ld(F, code)) if pad else (d, F)
+    hidden = torch.zeros((rows, ld2), dtype=gx.dtype, device=DEV)[:, :F]
     y = torch.full((rows, d), 7.0, dtype=gx.dtype, device=DEV)
-    B.scmoe_expert_ffn(gx, torch.from_numpy(offsets).to(DEV), rows, to_dev(W1, dtype), to_dev(b1, "f32"),
-                       to_dev(W2, dtype), to_dev(b2, "f32"), hidden, y, gelu_mode=gelu_mode)
+    B.scmoe_expert_ffn(gx, torch.from_numpy(offsets).to(DEV), rows, to_dev(W1, dtype, ld1), to_dev(b1, "f32"),
+                       to_dev(W2, dtype, ld2), to_dev(b2, "f32"), hidden, y, gelu_mode=gelu_mode)
     torch.cuda.synchronize()
     g = to_host(y)
     assert (g[K:] == 7.0).all()                       # rows past offsets[E] are not touched
@@ -167,6 +170,21 @@ def _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode, extra_rows=5, w_s
     (5, [0, 0, 40, 0, 9], 64, 128, "bf16", True, 0)])
 def test_expert_ffn_parity(oracle, E, lens, d, F, dtype, biases, gelu_mode):
     _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode)
+
+
+@pytest.mark.parametrize("E,lens,d,F,dtype", [
+    (3, [300, 0, 517], 256, 512, "bf16"),                   # 512- and 1024-byte rows: both get padded
+    (2, [130, 70], 128, 384, "f32"),                        # generic kernel with strided weights
+    (2, [33, 31], 72, 40, "bf16")])                         # widths the helper leaves dense
+def test_expert_ffn_padded_row_strides(oracle, E, lens, d, F, dtype):
+    """Weights and hidden scratch stored with padded rows (the padding holds huge values):
+    same result as the dense layout."""
+    code = B.BF16 if dtype == "bf16" else B.F32
+    assert B.scmoe_padded_ld(256, B.BF16) == 320 and B.scmoe_padded_ld(72, B.BF16) == 72
+    assert B.scmoe_padded_ld(128, B.F32) == 160 and B.scmoe_padded_ld(2048, B.BF16) == 2112
+    g, _ = _ffn_case(oracle, E, lens, d, F, dtype, True, 0, pad=True)
+    g0, _ = _ffn_case(oracle, E, lens, d, F, dtype, True, 0, pad=False)
+    assert np.array_equal(g, g0)
 
 
 @pytest.mark.parametrize("variant", [0, 1, 2])
@@ -222,8 +240,8 @@ def test_coef_gate_parity(oracle, mode, dtype, d):
 # -------------------------------------------------------------------------------- the layer
 
 def _layer_case(oracle, L, dtype, E, k, C_, shared, normalize=0, cg_mode=0, gelu_mode=0, residual=False,
-                two_streams=False):
-    D = DevLayer(L, dtype)
+                two_streams=False, pad_weights=False):
+    D = DevLayer(L, dtype, pad_weights)
     y, r = run_layer(D, k, C_, shared, normalize, cg_mode, gelu_mode, residual, two_streams)
     ref, rr = oracle.layer_forward(L["x_prev"], L["x_cur"], L, k=k, capacity_=C_, shared=int(shared),
                                    normalize=normalize, cg_mode=cg_mode, gelu_mode=gelu_mode,
@@ -249,7 +267,8 @@ def test_layer_bf16_mfma_path(oracle, k, shared, C_, normalize, cg, res, gelu):
     """bf16 layer on the MFMA path with gather-on-load: ragged T, binding capacity, drops."""
     L = inputs.make_layer(T=700, d=128, F=256, E=4, dtype="bf16", seed=11 + k, biases=True, cg_rows=cg,
                           w_scale=0.05)
-    y, r, ref, rr = _layer_case(oracle, L, "bf16", 4, k, C_, shared, normalize, cg, gelu, res, two_streams=shared)
+    y, r, ref, rr = _layer_case(oracle, L, "bf16", 4, k, C_, shared, normalize, cg, gelu, res, two_streams=shared,
+                                pad_weights=(C_ == 200 or C_ == 300))
     if shared and cg == 0 and not res:
         # dropped tokens: the expert term is exactly zero, so y equals the shared output
         dropped = r["dst_row"][:, 0] < 0
@@ -262,7 +281,7 @@ def test_scmoe2_two_routed_experts_plus_shared(oracle):
     """ScMoE-2: top-2 routing on x_prev with the shared expert on x_cur."""
     L = inputs.make_layer(T=600, d=128, F=256, E=8, dtype="bf16", seed=51, biases=True, w_scale=0.05)
     _layer_case(oracle, L, "bf16", 8, 2, 120, True, normalize=1)
-    _layer_case(oracle, L, "bf16", 8, 2, 100000, True, normalize=0, two_streams=True)
+    _layer_case(oracle, L, "bf16", 8, 2, 100000, True, normalize=0, two_streams=True, pad_weights=True)
 
 
 def test_layer_f32_generic_path_with_options(oracle):
@@ -290,13 +309,13 @@ def test_layer_is_deterministic(oracle):
 
 # --------------------------------------------------- full benchmark sizes, sampled rows
 
-def _full_size(oracle, name, n_sample, k=1, shared=True, normalize=0):
+def _full_size(oracle, name, n_sample, k=1, shared=True, normalize=0, pad_weights=False):
     """Routing compared for every token; output rows compared on a seeded sample (the
     oracle evaluates those tokens one by one)."""
     L, cfg = inputs.make_config(name)
     T, E = cfg["T"], cfg["E"]
     C_ = inputs.capacity(T, E, k, cfg["cf"])
-    D = DevLayer(L, cfg["dtype"])
+    D = DevLayer(L, cfg["dtype"], pad_weights)
     y, r = run_layer(D, k, C_, shared, normalize, two_streams=shared)
     xg = L["x_prev"] if shared else L["x_cur"]
     rr = oracle.route(xg, L, E, k, C_, normalize)
@@ -331,6 +350,8 @@ def test_full_size_skewed(oracle):
     assert (r["counts"][:3] == 1024).all()
 
 
-def test_full_size_large(oracle):
-    cfg, r = _full_size(oracle, "large", 48)
+@pytest.mark.parametrize("pad_weights", [True, False])
+def test_full_size_large(oracle, pad_weights):
+    """The benchmark workload, with dense weight rows (bench.py's default) and padded ones."""
+    cfg, r = _full_size(oracle, "large", 48, pad_weights=pad_weights)
     assert cfg["C"] == 2560
