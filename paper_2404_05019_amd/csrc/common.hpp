@@ -77,6 +77,9 @@ struct FfnArgs {
   void* hidden; int64_t ldh;       // [rows, F] scratch
   void* y; int64_t ldy;            // [rows, d]
   int gelu_mode;
+  // Fused output decode of the second GEMM (MFMA path only; scatter == nullptr: off):
+  //   y[scatter[r], :] = addend[scatter[r], :] + row_scale[scatter[r]] * (W2 . hidden[r] + b2)
+  const int32_t* scatter; const float* row_scale; const void* addend; int64_t ldadd;
 };
 
 int ffn_generic(const FfnArgs& a, int dtype, hipStream_t stream);

@@ -280,6 +280,11 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     for (int i = 0; i < MI; ++i) {
       const int mbase = crow0 + wave_m * CFG::TM + i * 32;
       if (mbase >= crow_end) continue;          // wave-uniform: the whole slab is past the segment
+      float rscale = 1.0f;                      // fused decode: the gate weight of this lane's row
+      if (p.scatter) {
+        const int mr = (mbase + lr < crow_end) ? mbase + lr : crow_end - 1;
+        rscale = p.row_scale[p.scatter[mr]];
+      }
 #pragma unroll
       for (int h = 0; h < 32 / CFG::STG_ROWS; ++h) {
         const int sr = lr - h * CFG::STG_ROWS;  // this lane's row inside the staged rows
@@ -301,6 +306,10 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
               for (int q = 0; q < 4; ++q)
                 v[q] = (p.gelu_mode == SCMOE_GELU_TANH) ? gelu_tanh_fast(v[q]) : gelu_erf_fast(v[q]);
             }
+            if (p.scatter) {
+#pragma unroll
+              for (int q = 0; q < 4; ++q) v[q] *= rscale;
+            }
             uint2 o;
             o.x = cvt_pk_bf16(v[0], v[1]);
             o.y = cvt_pk_bf16(v[2], v[3]);
@@ -312,11 +321,22 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
         for (int r0 = 0; r0 < CFG::STG_ROWS; r0 += 8) {
           const int r = r0 + (lane >> 3);       // 8 lanes of 16 bytes per 128-byte row
           const int c = lane & 7;
-          const uint4 o = *reinterpret_cast<const uint4*>(stg + r * CFG::STG_ROW + ((c ^ swz<8>(r)) << 4));
+          uint4 o = *reinterpret_cast<const uint4*>(stg + r * CFG::STG_ROW + ((c ^ swz<8>(r)) << 4));
           const int m = mbase + h * CFG::STG_ROWS + r;
           const int n = cn0 + wave_n * CFG::TN + c * 8;
-          if (m < crow_end && n < p.N)
-            *reinterpret_cast<uint4*>(p.C + (static_cast<int64_t>(m) * p.ldc + n) * 2) = o;
+          if (m < crow_end && n < p.N) {
+            int64_t orow = m;
+            if (p.scatter) {
+              // output decode: this packed row belongs to token orow; add the row already there
+              orow = p.scatter[m];
+              const uint4 a = *reinterpret_cast<const uint4*>(p.addend + (orow * p.ldadd + n) * 2);
+              o.x = add_bf16x2(o.x, a.x);
+              o.y = add_bf16x2(o.y, a.y);
+              o.z = add_bf16x2(o.z, a.z);
+              o.w = add_bf16x2(o.w, a.w);
+            }
+            *reinterpret_cast<uint4*>(p.C + (orow * p.ldc + n) * 2) = o;
+          }
         }
       }
     }
@@ -414,6 +434,10 @@ int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   g2.N = a.d;
   g2.Kd = a.F;
   g2.gelu_mode = a.gelu_mode;
+  g2.scatter = a.scatter;
+  g2.row_scale = a.row_scale;
+  g2.addend = static_cast<const unsigned char*>(a.addend);
+  g2.ldadd = a.ldadd;
   return launch_variant<false>(g2, a.max_rows, stream);
 }
 

@@ -101,7 +101,7 @@ __global__ void set_pair(int32_t* p, int a, int b) {
 static int expert_ffn_any(const FfnArgs& a, int dtype, hipStream_t stream) {
   if (a.max_rows <= 0) return SCMOE_OK;
   if (dtype == SCMOE_BF16 && ffn_mfma_supported(a.d, a.F)) return ffn_mfma_bf16(a, stream);
-  if (a.gather != nullptr) return SCMOE_ERR_ARG;  // the generic kernel reads packed rows only
+  if (a.gather != nullptr || a.scatter != nullptr) return SCMOE_ERR_ARG;  // packed rows in, packed rows out only
   return ffn_generic(a, dtype, stream);
 }
 
@@ -157,8 +157,12 @@ static int copy_routing(const scmoe_desc* D, const LayerWs& w, const scmoe_routi
 }
 
 // gate -> encode -> experts on `stream`; leaves y_perm, dst_row, gate_w in the workspace.
+// With fused_y != nullptr the second GEMM decodes in its epilogue instead (Sec. 2.2 "output
+// decode"): row r goes to fused_y[src_token[r], :] += gate_w * expert output, on top of what
+// the shared expert has written there; `before_ffn` (optional) is waited for first.
 static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const scmoe_weights* W,
-                        const LayerWs& w, hipStream_t stream) {
+                        const LayerWs& w, hipStream_t stream, void* fused_y = nullptr, int64_t ld_fused = 0,
+                        hipEvent_t before_ffn = nullptr) {
   SCMOE_TRY(gate_topk(x, ldx, D->dtype, W->W_g, W->bias, D->T, D->d, D->E, D->k, D->normalize,
                       w.expert_idx, w.gate_w, nullptr, stream));
   const bool gol = gather_on_load(D);
@@ -177,6 +181,14 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
   a.hidden = w.hidden; a.ldh = w.ldh;
   a.y = w.y_perm; a.ldy = D->d;
   a.gelu_mode = D->gelu_mode;
+  if (fused_y) {
+    if (before_ffn) {
+      hipError_t e = hipStreamWaitEvent(stream, before_ffn, 0);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+    a.y = fused_y; a.ldy = ld_fused;
+    a.scatter = w.src_token; a.row_scale = w.gate_w; a.addend = fused_y; a.ldadd = ld_fused;
+  }
   return expert_ffn_any(a, D->dtype, stream);
 }
 
@@ -298,12 +310,28 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   // shared expert on the current-layer representation (Eq. (6)/(7)): independent of routing
   hipLaunchKernelGGL(set_pair, dim3(1), dim3(64), 0, s_shared, w.offsets_shared, 0, D->T);
   SCMOE_TRY(launch_status());
+  // Fused output decode: for top-1 routing without coefficient gate or residual, on the MFMA
+  // path, the shared expert writes y and the routed GEMM2 adds its gate-weighted rows into
+  // y[src_token[r]] (every row is written once, dropped tokens keep SE(x_cur)): no y_perm
+  // round trip and no combine kernel.  Needs y not to overlap the inputs, which are still
+  // being read when y is first written.
+  const size_t eb = elem_bytes(D->dtype);
+  auto overlaps = [&](const void* a, int64_t lda_, const void* b, int64_t ldb_) {
+    const unsigned char* a0 = static_cast<const unsigned char*>(a);
+    const unsigned char* b0 = static_cast<const unsigned char*>(b);
+    const size_t an = static_cast<size_t>(D->T) * lda_ * eb, bn = static_cast<size_t>(D->T) * ldb_ * eb;
+    return a0 < b0 + bn && b0 < a0 + an;
+  };
+  const bool fused = D->k == 1 && D->cg_mode == SCMOE_CG_NONE && !residual && gather_on_load(D) &&
+                     !overlaps(y, ldy, x_prev, ld_prev) && !overlaps(y, ldy, x_cur, ld_cur);
   FfnArgs se{};
   se.x = x_cur; se.ldx = ld_cur; se.gather = nullptr; se.offsets = w.offsets_shared;
   se.max_rows = D->T; se.E = 1; se.d = D->d; se.F = D->F;
   se.W1 = W->W1s; se.ldw1 = ld_or(W->ld_w1, D->d); se.b1 = W->b1s;
   se.W2 = W->W2s; se.ldw2 = ld_or(W->ld_w2, D->F); se.b2 = W->b2s;
-  se.hidden = w.hidden_s; se.ldh = w.ldh; se.y = w.s; se.ldy = D->d; se.gelu_mode = D->gelu_mode;
+  se.hidden = w.hidden_s; se.ldh = w.ldh; se.gelu_mode = D->gelu_mode;
+  se.y = fused ? y : w.s;
+  se.ldy = fused ? ldy : D->d;
   SCMOE_TRY(expert_ffn_any(se, D->dtype, s_shared));
   if (D->cg_mode != SCMOE_CG_NONE)
     SCMOE_TRY(coef_gate(x_cur, ld_cur, D->dtype, W->W_cg, D->cg_mode, D->T, D->d, w.coef, s_shared));
@@ -312,6 +340,10 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
     if (e != hipSuccess) return hip_fail(e);
   }
   // routed experts on the preceding-layer representation
+  if (fused) {
+    SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, y, ldy, two ? ev->join : nullptr));
+    return copy_routing(D, w, routing, sm);
+  }
   SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm));
   if (two) {
     hipError_t e = hipStreamWaitEvent(sm, ev->join, 0);

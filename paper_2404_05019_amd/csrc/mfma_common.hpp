@@ -44,6 +44,12 @@ struct GemmArgs {
   int E, N, Kd;
   int nt;                   // column tiles
   int gelu_mode;
+  // Fused output decode (optional; scatter == nullptr stores C[r, :] as is).  Packed row r
+  // is written to row t = scatter[r] of C as  addend[t, :] + row_scale[t] * (sum + bias).
+  const int32_t* scatter;
+  const float* row_scale;
+  const unsigned char* addend;   // bf16 [*, N], row stride ldadd; may be C itself
+  int64_t ldadd;
 };
 
 // erf-form GELU for the bf16 epilogue: erf(v / sqrt 2) ~ v * P(v^2) on |v| <= 3 sqrt 2,
@@ -76,6 +82,13 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
   f32x2_t f = {a, b};
   bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
   return __builtin_bit_cast(uint32_t, h);
+}
+
+// Sum of two pairs of bf16 in fp32, rounded once.
+__device__ __forceinline__ uint32_t add_bf16x2(uint32_t a, uint32_t b) {
+  const float lo = __uint_as_float(a << 16) + __uint_as_float(b << 16);
+  const float hi = __uint_as_float(a & 0xffff0000u) + __uint_as_float(b & 0xffff0000u);
+  return cvt_pk_bf16(lo, hi);
 }
 
 // Workgroup barrier of the main loops.  __syncthreads() carries workgroup-scope fences, for

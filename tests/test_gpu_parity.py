@@ -297,6 +297,25 @@ def test_shared_expert_moe_is_scmoe_with_equal_inputs(oracle):
     _layer_case(oracle, L, "bf16", 4, 1, 200, True)
 
 
+def test_layer_in_place_output(oracle):
+    """y may be the same buffer as x_cur: the layer then must not write y before it has read
+    its inputs (the fused decode is skipped for overlapping buffers)."""
+    L = inputs.make_layer(T=900, d=128, F=256, E=4, dtype="bf16", seed=61, biases=True, w_scale=0.05)
+    D = DevLayer(L, "bf16")
+    ref, rr = oracle.layer_forward(L["x_prev"], L["x_cur"], L, k=1, capacity_=300, shared=1)
+    desc = B.make_desc(D.T, D.d, D.F, D.E, 1, 300, D.code)
+    ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    y = D.x_cur.clone()
+    B.scmoe_layer_forward(desc, D.x_prev, y, D.weights, y, ws)
+    torch.cuda.synchronize()
+    assert relerr(to_host(y), ref) <= TOL["bf16"]
+    y2 = torch.empty_like(y)
+    B.scmoe_layer_forward(desc, D.x_prev, D.x_cur, D.weights, y2, ws)      # separate buffers: fused decode
+    torch.cuda.synchronize()
+    assert relerr(to_host(y2), ref) <= TOL["bf16"]
+    assert relerr(to_host(y2), to_host(y)) <= 1e-2
+
+
 def test_layer_is_deterministic(oracle):
     L = inputs.make_layer(T=3000, d=128, F=256, E=8, dtype="bf16", seed=41, w_scale=0.05)
     D = DevLayer(L, "bf16")
