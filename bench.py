@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="1: all kernels in order on one stream; 2: shared expert on a second stream")
     ap.add_argument("--gemm-variant", type=int, default=None)
+    ap.add_argument("--no-ffn-workspace", action="store_true",
+                    help="time the scmoe_expert_ffn leg without its optional scratch (no split-K of the last round)")
     ap.add_argument("--padded-weights", action="store_true",
                     help="store the expert weights with the padded row stride of scmoe_padded_ld "
                          "instead of dense rows")
@@ -119,8 +121,11 @@ def main():
     ms_gate = time_region(torch, lambda: B.scmoe_gate_top1(D.x_prev, D.Wg, D.bias, idx, gw), n_ops, 3)
     ms_disp = time_region(torch, lambda: B.scmoe_dispatch(D.x_prev, idx, E, 1, C_, counts, offsets, dst_row,
                                                           src_token, x_perm, dws), n_ops, 3)
+    ffn_ws = torch.empty(max(B.scmoe_expert_ffn_workspace_bytes(D.code, d, F), 16), dtype=torch.uint8, device=DEV)
+    if args.no_ffn_workspace:
+        ffn_ws = None
     ms_ffn = time_region(torch, lambda: B.scmoe_expert_ffn(x_perm, offsets, rows, D.W1, D.b1, D.W2, D.b2, hidden,
-                                                           y_perm), args.steps, 2)
+                                                           y_perm, workspace=ffn_ws), args.steps, 2)
     ms_comb = time_region(torch, lambda: B.scmoe_combine(y_perm, dst_row, gw, 1, s_out, None, None, y), n_ops, 3)
 
     if args.calibrate_copy:

@@ -210,6 +210,12 @@ int scmoe_dispatch(const void* x, int64_t ldx, int32_t dtype, const int32_t* exp
  * b2 [E, d] fp32 or NULL.  hidden: caller scratch [max_rows, F] in `dtype`, row stride ldh.
  * All strides are in elements, multiples of 8, and at least the row width.
  * bf16: fp32 accumulation, hidden and y_perm rounded to bf16 (RNE) on store.
+ * workspace: optional device scratch of scmoe_expert_ffn_workspace_bytes bytes (16-byte
+ * aligned).  With it the bf16 kernels cut the tiles of the last, partly filled round of
+ * workgroups along K and add the parts up in a fixed order (results stay run-to-run
+ * identical; they may differ in the last bit from a call without workspace).  NULL, or
+ * fewer bytes than asked for: that round runs unsplit.  Calls that may overlap in time
+ * need separate workspaces.
  * With E = 1 and offsets = {0, T} this is the dense MLP used for the shared expert
  * (Eq. (6)).
  */
@@ -218,7 +224,11 @@ int scmoe_expert_ffn(const void* x_perm, int64_t ld_perm, int32_t dtype,
                      int32_t F, const void* W1, int64_t ldw1, const float* b1,
                      const void* W2, int64_t ldw2, const float* b2, void* hidden,
                      int64_t ldh, void* y_perm, int64_t ldy, int32_t gelu_mode,
-                     void* stream);
+                     void* workspace, size_t ws_bytes, void* stream);
+
+/* Bytes of optional scratch scmoe_expert_ffn can use for these widths (0 when the shape
+ * takes a path that needs none).  `out` is a host pointer. */
+int scmoe_expert_ffn_workspace_bytes(int32_t dtype, int32_t d, int32_t F, size_t* out);
 
 /*
  * Output decode (Sec. 2.2) fused with the merge of Eq. (6)/(7):

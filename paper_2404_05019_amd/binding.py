@@ -20,6 +20,7 @@ MAX_EXPERTS = 64
 EXPORTS = ["scmoe_status_string", "scmoe_last_hip_error", "scmoe_set_gemm_variant", "scmoe_padded_ld", "scmoe_capacity",
            "scmoe_gate_top1",
            "scmoe_gate_top2", "scmoe_dispatch_workspace_bytes", "scmoe_dispatch", "scmoe_expert_ffn",
+           "scmoe_expert_ffn_workspace_bytes",
            "scmoe_combine", "scmoe_coef_gate", "scmoe_workspace_bytes", "scmoe_layer_forward",
            "moe_topk_layer_forward", "moe_top2_layer_forward"]
 
@@ -70,7 +71,8 @@ def lib():
         _lib.scmoe_dispatch.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i64,
                                         vp, sz, vp]
         _lib.scmoe_expert_ffn.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, vp, i64, vp, vp, i64, vp, vp, i64,
-                                          vp, i64, i32, vp]
+                                          vp, i64, i32, vp, sz, vp]
+        _lib.scmoe_expert_ffn_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
         _lib.scmoe_combine.argtypes = [vp, i64, i32, vp, vp, i32, i32, i32, vp, i64, vp, i64, vp, vp, i64, vp]
         _lib.scmoe_coef_gate.argtypes = [vp, i64, i32, vp, i32, i32, i32, vp, vp]
         _lib.scmoe_workspace_bytes.argtypes = [C.POINTER(Desc), C.POINTER(sz)]
@@ -172,12 +174,20 @@ def scmoe_dispatch(x, expert_idx, E, k, capacity, counts, offsets, dst_row, src_
                                 _stream(stream)), "scmoe_dispatch")
 
 
+def scmoe_expert_ffn_workspace_bytes(dtype, d, F):
+    out = C.c_size_t(0)
+    _check(lib().scmoe_expert_ffn_workspace_bytes(dtype, d, F, C.byref(out)), "scmoe_expert_ffn_workspace_bytes")
+    return out.value
+
+
 def scmoe_expert_ffn(x_perm, offsets, max_rows, W1, b1, W2, b2, hidden, y_perm, gelu_mode=GELU_ERF,
-                     stream=None):
+                     workspace=None, stream=None):
     E, F, d = W1.shape
     _check(lib().scmoe_expert_ffn(_ptr(x_perm), _ld(x_perm), dtype_code(x_perm), _ptr(offsets), max_rows, E,
                                   d, F, _ptr(W1), _ldw(W1), _ptr(b1), _ptr(W2), _ldw(W2), _ptr(b2), _ptr(hidden),
-                                  _ld(hidden), _ptr(y_perm), _ld(y_perm), gelu_mode, _stream(stream)),
+                                  _ld(hidden), _ptr(y_perm), _ld(y_perm), gelu_mode, _ptr(workspace),
+                                  0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                  _stream(stream)),
            "scmoe_expert_ffn")
 
 

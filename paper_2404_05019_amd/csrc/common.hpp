@@ -80,6 +80,8 @@ struct FfnArgs {
   // Fused output decode of the second GEMM (MFMA path only; scatter == nullptr: off):
   //   y[scatter[r], :] = addend[scatter[r], :] + row_scale[scatter[r]] * (W2 . hidden[r] + b2)
   const int32_t* scatter; const float* row_scale; const void* addend; int64_t ldadd;
+  // Scratch of the MFMA path (split-K of the last round of tiles); may be nullptr: no split.
+  void* scratch; size_t scratch_bytes;
 };
 
 int ffn_generic(const FfnArgs& a, int dtype, hipStream_t stream);
@@ -95,5 +97,6 @@ inline int64_t padded_ld(int64_t width, int dtype) {
   return ((width * eb) % 512 == 0) ? width + 128 / eb : width;
 }
 bool ffn_mfma_supported(int d, int F);
+size_t ffn_mfma_scratch_bytes();   // scratch the MFMA path can use (16-byte aligned)
 
 }  // namespace scmoe

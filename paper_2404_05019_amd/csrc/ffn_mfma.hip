@@ -65,17 +65,18 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // ---- tile schedule ------------------------------------------------------------------------
-  const TileSchedule<BM, BN, CFG::GM> sched(p);
-  int L = sched.L;
-  const int Lend = sched.Lend, nslots = sched.nslots;
-  if (L >= Lend) return;
-  auto locate = [&](int l, int& e, int& row0, int& row_end, int& n0) { sched.locate(l, e, row0, row_end, n0); };
+  const int nk_all = p.Kd / BK;
+  const TileSchedule<BM, BN, CFG::GM> sched(p, nk_all, p.splitk_part != nullptr);
+  const int nslots = sched.nslots;
+  int it = blockIdx.x >> 3;                // work item: a tile, or one K-part of a tile of the last round
+  if (it >= sched.nitems) return;
+  int nk = nk_all;                         // k-tiles of the current item
 
   // ---- per-lane source addresses of the direct-to-LDS loads -------------------------------
   const unsigned char* aptr[CFG::A_PER_WAVE];
   const unsigned char* bptr[CFG::B_PER_WAVE];
-  auto set_ptrs = [&](int e, int row0, int row_end, int n0) {
-    const unsigned char* We = p.W + static_cast<int64_t>(e) * p.N * p.ldw * 2;
+  auto set_ptrs = [&](int e, int row0, int row_end, int n0, int kb) {   // kb: first k-tile of the item
+    const unsigned char* We = p.W + static_cast<int64_t>(e) * p.N * p.ldw * 2 + static_cast<int64_t>(kb) * RB;
 #pragma unroll
     for (int i = 0; i < CFG::A_PER_WAVE; ++i) {
       const int row = (wave * CFG::A_PER_WAVE + i) * CFG::RPL + lane / CPR;
@@ -83,7 +84,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       int m = row0 + row;
       if (m > row_end - 1) m = row_end - 1;      // rows past the segment re-read its last row
       const int64_t src = p.gather ? p.gather[m] : m;
-      aptr[i] = p.A + src * p.lda * 2 + kc * 16;
+      aptr[i] = p.A + src * p.lda * 2 + kc * 16 + static_cast<int64_t>(kb) * RB;
     }
 #pragma unroll
     for (int i = 0; i < CFG::B_PER_WAVE; ++i) {
@@ -106,7 +107,6 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(bptr[i] + static_cast<int64_t>(kt) * RB),
                                        SCMOE_LDS_PTR(sb + i * 1024), 16, 0, 0);
   };
-  const int nk = p.Kd / BK;
   auto issue_prologue = [&]() {
 #pragma unroll
     for (int t = 0; t < NS; ++t)
@@ -167,9 +167,20 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[i][j], 0, 0, 0);
   };
 
-  int e, row0, row_end, n0;
-  locate(L, e, row0, row_end, n0);
-  set_ptrs(e, row0, row_end, n0);
+  int e, row0, row_end, n0, part;
+  auto setup = [&](int item) {
+    int l;
+    sched.item(item, l, part);
+    sched.locate(l, e, row0, row_end, n0);
+    int kb = 0;
+    nk = nk_all;
+    if (part >= 0) {
+      kb = part * nk_all / sched.S;
+      nk = (part + 1) * nk_all / sched.S - kb;
+    }
+    set_ptrs(e, row0, row_end, n0, kb);
+  };
+  setup(it);
   issue_prologue();
   for (;;) {
 #pragma unroll
@@ -259,14 +270,71 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     }
 
     // ---- next tile: its first k-tiles are requested before this tile's epilogue -----------
-    const int Ln = L + nslots;
-    const bool more = Ln < Lend;
-    const int ce = e, crow0 = row0, crow_end = row_end, cn0 = n0;
+    const int itn = it + nslots;
+    const bool more = itn < sched.nitems;
+    const int ce = e, crow0 = row0, crow_end = row_end, cn0 = n0, cpart = part, cw = it - sched.full;
     lds_barrier();                    // every wave holds its last fragments: LDS is free
     if (more) {
-      locate(Ln, e, row0, row_end, n0);
-      set_ptrs(e, row0, row_end, n0);
+      setup(itn);
       issue_prologue();
+    }
+
+    // ---- split-K items: leave the partial sums in scratch; the last part to arrive adds all
+    // parts up in part order (so the result does not depend on the arrival order) and goes
+    // on to the epilogue, the others are done.  No workgroup waits for another one.
+    // The partial sums and the counter move with relaxed device-scope atomics, which go past
+    // the caches that are not shared by the whole device, ordered by a plain wait for the
+    // stores; device-scope fences would write back and invalidate the whole L2 of the XCD on
+    // every use, which costs more than the split saves.
+    bool finish = true;
+    if (cpart >= 0) {
+      constexpr int TILE = BM * BN;
+      constexpr int FRAGS = MI * NJ * 4;                              // 16-byte pieces per lane
+      const int S = sched.S;
+      const size_t slot0 = static_cast<size_t>(sched.xcd) * nslots;   // this XCD's scratch slots
+      // piece (i, j, g) of wave w and lane l sits at float4 index ((w * FRAGS + (i*NJ+j)*4 + g) * 64 + l
+      float* mine = p.splitk_part + (slot0 + cw) * TILE + ((wave * FRAGS) * 64 + lane) * 4;
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4_t v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+            store16_device_scope(mine + (((i * NJ + j) * 4 + g) * 64) * 4, v);
+          }
+      wait_vm(std::integral_constant<int, 0>{});                      // this wave's stores have been performed
+      lds_barrier();
+      int* flag = reinterpret_cast<int*>(smem + NS * STAGE);          // first word of wave 0's epilogue patch
+      if (tid == 0) {
+        int* cnt = p.splitk_count + slot0 + cw / S;
+        const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == S - 1)                                             // all parts are in: ready for the next launch
+          __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *flag = old;
+      }
+      lds_barrier();
+      const int old = *flag;
+      lds_barrier();                                                  // the patch is reused below
+      finish = old == S - 1;
+      if (finish) {
+        const float* first = p.splitk_part + (slot0 + (cw / S) * S) * TILE + ((wave * FRAGS) * 64 + lane) * 4;
+        for (int q = 0; q < S; ++q) {
+          const float* src = first + static_cast<size_t>(q) * TILE;
+#pragma unroll
+          for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+              f32x4_t t[4];
+              load4x16_device_scope(src + (((i * NJ + j) * 4) * 64) * 4, t[0], t[1], t[2], t[3]);
+#pragma unroll
+              for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                  acc[i][j][4 * g + c] = (q == 0) ? t[g][c] : acc[i][j][4 * g + c] + t[g][c];
+            }
+        }
+      }
     }
 
     // ---- epilogue: bias, activation, bf16; rows re-assembled in LDS, 16-byte stores ---------
@@ -279,7 +347,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int mbase = crow0 + wave_m * CFG::TM + i * 32;
-      if (mbase >= crow_end) continue;          // wave-uniform: the whole slab is past the segment
+      if (!finish || mbase >= crow_end) continue;   // wave-uniform: not the last part / slab past the segment
       float rscale = 1.0f;                      // fused decode: the gate weight of this lane's row
       if (p.scatter) {
         const int mr = (mbase + lr < crow_end) ? mbase + lr : crow_end - 1;
@@ -341,7 +409,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       }
     }
     if (!more) break;
-    L = Ln;
+    it = itn;
   }
 }
 
@@ -387,6 +455,12 @@ static int launch_gemm(GemmArgs a, int max_rows, hipStream_t stream) {
   int slots = (mtb * a.nt + 7) / 8;                            // tiles per XCD, upper bound
   const int resident = (num_cus() / 8) * CFG::WG_PER_CU;       // workgroups one XCD holds at once
   if (slots > resident) slots = resident;
+  // the split-K scratch is laid out for 8 * slots partial tiles of this shape
+  if (8 * slots > SPLITK_PARTS ||
+      static_cast<size_t>(8) * slots * CFG::BM * CFG::BN * 4 > SPLITK_WS_BYTES - SPLITK_COUNT_BYTES) {
+    a.splitk_part = nullptr;
+    a.splitk_count = nullptr;
+  }
   hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT>), dim3(8 * slots), dim3(CFG::THREADS), CFG::LDS_BYTES,
                      stream, a);
   return launch_status();
@@ -401,9 +475,25 @@ static int launch_variant(const GemmArgs& a, int max_rows, hipStream_t stream) {
   }
 }
 
+__global__ void zero_ints(int* p, int n) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
+}
+
+size_t ffn_mfma_scratch_bytes() { return SPLITK_WS_BYTES; }
+
 int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   if (!ffn_mfma_supported(a.d, a.F)) return SCMOE_ERR_ARG;
   if (a.max_rows <= 0) return SCMOE_OK;
+  int* counters = nullptr;
+  float* parts = nullptr;
+  if (a.scratch != nullptr && a.scratch_bytes >= SPLITK_WS_BYTES) {
+    // arrival counters first (every launch leaves them at zero again), then the partial tiles
+    counters = static_cast<int*>(a.scratch);
+    parts = reinterpret_cast<float*>(static_cast<unsigned char*>(a.scratch) + SPLITK_COUNT_BYTES);
+    hipLaunchKernelGGL(zero_ints, dim3(1), dim3(256), 0, stream, counters, SPLITK_PARTS);
+    int st0 = launch_status();
+    if (st0 != SCMOE_OK) return st0;
+  }
   GemmArgs g1{};
   g1.A = static_cast<const unsigned char*>(a.x);
   g1.lda = a.ldx;
@@ -418,6 +508,8 @@ int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   g1.N = a.F;
   g1.Kd = a.d;
   g1.gelu_mode = a.gelu_mode;
+  g1.splitk_part = parts;
+  g1.splitk_count = counters;
   int st = launch_variant<true>(g1, a.max_rows, stream);
   if (st != SCMOE_OK) return st;
   GemmArgs g2{};
@@ -438,6 +530,8 @@ int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   g2.row_scale = a.row_scale;
   g2.addend = static_cast<const unsigned char*>(a.addend);
   g2.ldadd = a.ldadd;
+  g2.splitk_part = parts;
+  g2.splitk_count = counters;
   return launch_variant<false>(g2, a.max_rows, stream);
 }
 

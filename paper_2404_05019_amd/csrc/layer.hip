@@ -52,6 +52,7 @@ struct LayerWs {
   int32_t* expert_idx; float* gate_w; int32_t* counts; int32_t* offsets; int32_t* dst_row;
   int32_t* src_token; int32_t* offsets_shared; float* coef; void* disp_ws; size_t disp_bytes;
   void* x_perm; void* hidden; void* y_perm; void* hidden_s; void* s;
+  void* scratch_r; void* scratch_s; size_t scratch_bytes;   // GEMM scratch of the routed / shared chain
   int64_t ldh;   // row stride of hidden and hidden_s
   size_t total;
 };
@@ -82,7 +83,10 @@ static LayerWs carve(const scmoe_desc* D, void* base, bool shared) {
   w.ldh = padded_ld(D->F, D->dtype);
   w.hidden = take(rows * w.ldh * eb);
   w.y_perm = take(rows * D->d * eb);
+  w.scratch_bytes = (D->dtype == SCMOE_BF16 && ffn_mfma_supported(D->d, D->F)) ? ffn_mfma_scratch_bytes() : 0;
+  w.scratch_r = take(w.scratch_bytes);
   if (shared) {
+    w.scratch_s = take(w.scratch_bytes);   // the two chains may run at the same time
     w.hidden_s = take(static_cast<size_t>(D->T) * w.ldh * eb);
     w.s = take(static_cast<size_t>(D->T) * D->d * eb);
   }
@@ -181,6 +185,7 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
   a.hidden = w.hidden; a.ldh = w.ldh;
   a.y = w.y_perm; a.ldy = D->d;
   a.gelu_mode = D->gelu_mode;
+  a.scratch = w.scratch_bytes ? w.scratch_r : nullptr; a.scratch_bytes = w.scratch_bytes;
   if (fused_y) {
     if (before_ffn) {
       hipError_t e = hipStreamWaitEvent(stream, before_ffn, 0);
@@ -239,7 +244,7 @@ extern "C" int scmoe_expert_ffn(const void* x_perm, int64_t ld_perm, int32_t dty
                                 int32_t F, const void* W1, int64_t ldw1, const float* b1,
                                 const void* W2, int64_t ldw2, const float* b2, void* hidden,
                                 int64_t ldh, void* y_perm, int64_t ldy, int32_t gelu_mode,
-                                void* stream) {
+                                void* workspace, size_t ws_bytes, void* stream) {
   if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
   if (max_rows < 0 || E < 1 || d <= 0 || F <= 0 || (d % 8) || (F % 8)) return SCMOE_ERR_SHAPE;
   if (gelu_mode != SCMOE_GELU_ERF && gelu_mode != SCMOE_GELU_TANH) return SCMOE_ERR_ARG;
@@ -254,7 +259,19 @@ extern "C" int scmoe_expert_ffn(const void* x_perm, int64_t ld_perm, int32_t dty
   a.max_rows = max_rows; a.E = E; a.d = d; a.F = F;
   a.W1 = W1; a.ldw1 = ldw1; a.b1 = b1; a.W2 = W2; a.ldw2 = ldw2; a.b2 = b2;
   a.hidden = hidden; a.ldh = ldh; a.y = y_perm; a.ldy = ldy; a.gelu_mode = gelu_mode;
+  if (workspace != nullptr) {
+    if (!aligned16(workspace)) return SCMOE_ERR_SHAPE;
+    a.scratch = workspace; a.scratch_bytes = ws_bytes;
+  }
   return expert_ffn_any(a, dtype, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int scmoe_expert_ffn_workspace_bytes(int32_t dtype, int32_t d, int32_t F, size_t* out) {
+  if (!out) return SCMOE_ERR_NULL;
+  if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
+  if (d <= 0 || F <= 0) return SCMOE_ERR_SHAPE;
+  *out = (dtype == SCMOE_BF16 && ffn_mfma_supported(d, F)) ? ffn_mfma_scratch_bytes() : 0;
+  return SCMOE_OK;
 }
 
 extern "C" int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out) {
@@ -330,6 +347,7 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   se.W1 = W->W1s; se.ldw1 = ld_or(W->ld_w1, D->d); se.b1 = W->b1s;
   se.W2 = W->W2s; se.ldw2 = ld_or(W->ld_w2, D->F); se.b2 = W->b2s;
   se.hidden = w.hidden_s; se.ldh = w.ldh; se.gelu_mode = D->gelu_mode;
+  se.scratch = w.scratch_bytes ? w.scratch_s : nullptr; se.scratch_bytes = w.scratch_bytes;
   se.y = fused ? y : w.s;
   se.ldy = fused ? ldy : D->d;
   SCMOE_TRY(expert_ffn_any(se, D->dtype, s_shared));

@@ -14,6 +14,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 #define SCMOE_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define SCMOE_GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -50,7 +51,18 @@ struct GemmArgs {
   const float* row_scale;
   const unsigned char* addend;   // bf16 [*, N], row stride ldadd; may be C itself
   int64_t ldadd;
+  // Split-K of the last, partly filled round of tiles (optional; splitk_part == nullptr: off).
+  float* splitk_part;            // SPLITK_PARTS partial tiles of BM x BN floats
+  int* splitk_count;             // SPLITK_PARTS arrival counters, zero between launches
 };
+
+// Scratch of the split-K tail: per XCD as many partial tiles as workgroups are resident
+// there (64 at most on a 256-CU device: 32 CUs x 2 workgroups), 256 KiB each at most.
+constexpr int SPLITK_PARTS = 8 * 64;
+constexpr size_t SPLITK_TILE_BYTES = 256 * 256 * 4;
+constexpr size_t SPLITK_COUNT_BYTES = SPLITK_PARTS * sizeof(int);
+constexpr size_t SPLITK_WS_BYTES = SPLITK_COUNT_BYTES + 8 * 32 * SPLITK_TILE_BYTES;
+constexpr int SPLITK_MAX = 8;    // most parts one tile is cut into
 
 // erf-form GELU for the bf16 epilogue: erf(v / sqrt 2) ~ v * P(v^2) on |v| <= 3 sqrt 2,
 // saturated outside (degree-8 minimax fit; |error of GELU| < 6e-5, far below the bf16
@@ -91,6 +103,25 @@ __device__ __forceinline__ uint32_t add_bf16x2(uint32_t a, uint32_t b) {
   return cvt_pk_bf16(lo, hi);
 }
 
+// 16-byte store / loads at device scope (sc1: past the caches that are not shared by the whole
+// device), for data handed from one workgroup to another inside a kernel.  The store is not
+// waited for here (follow it with a vmcnt(0) wait before publishing); the load reads four
+// pieces 1 KiB apart and returns when they have arrived.
+__device__ __forceinline__ void store16_device_scope(float* p, f32x4_t v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void load4x16_device_scope(const float* p, f32x4_t& a, f32x4_t& b, f32x4_t& c, f32x4_t& d) {
+  asm volatile(
+      "global_load_dwordx4 %0, %4, off sc1\n\t"
+      "global_load_dwordx4 %1, %4, off offset:1024 sc1\n\t"
+      "global_load_dwordx4 %2, %4, off offset:2048 sc1\n\t"
+      "global_load_dwordx4 %3, %4, off offset:3072 sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      : "=&v"(a), "=&v"(b), "=&v"(c), "=&v"(d)
+      : "v"(p)
+      : "memory");
+}
+
 // Workgroup barrier of the main loops.  __syncthreads() carries workgroup-scope fences, for
 // which the compiler drains the vector-memory counter (s_waitcnt vmcnt(0)): that would wait
 // for every global -> LDS copy in flight, including the ones requested for later k-tiles, and
@@ -109,16 +140,44 @@ template <int BM, int BN, int GM>
 struct TileSchedule {
   int mt_total, nt, E;
   const int32_t* offsets;
-  int L, Lend, nslots;
+  int nslots;
+  // Work items of this XCD: its `full` tiles that fill whole rounds of nslots workgroups, then
+  // the `rem` tiles of the last round, each cut along K into S parts so that the round keeps
+  // (nearly) all workgroups busy.  Item it < full is tile c0 + it; item full + w is part w % S
+  // of tile c0 + full + w / S.  A workgroup takes items slot, slot + nslots, ...
+  int c0, full, rem, S, nitems, xcd;
 
-  __device__ __forceinline__ TileSchedule(const GemmArgs& p) : mt_total(0), nt(p.nt), E(p.E), offsets(p.offsets) {
+  __device__ __forceinline__ TileSchedule(const GemmArgs& p, int nk, bool can_split)
+      : mt_total(0), nt(p.nt), E(p.E), offsets(p.offsets) {
     for (int q = 0; q < E; ++q) mt_total += (offsets[q + 1] - offsets[q] + BM - 1) / BM;
     const int total = mt_total * nt;
     const int chunk = (total + 7) >> 3;
-    const int x = blockIdx.x & 7;
+    xcd = blockIdx.x & 7;
     nslots = gridDim.x >> 3;
-    L = x * chunk + (blockIdx.x >> 3);
-    Lend = ((x + 1) * chunk < total) ? (x + 1) * chunk : total;
+    c0 = xcd * chunk;
+    int c1 = (xcd + 1) * chunk < total ? (xcd + 1) * chunk : total;
+    const int n = c1 > c0 ? c1 - c0 : 0;
+    full = (n / nslots) * nslots;
+    rem = n - full;
+    S = 1;
+    if (can_split && rem > 0) {
+      S = nslots / rem;
+      if (S > SPLITK_MAX) S = SPLITK_MAX;
+      if (S > nk) S = nk;
+      if (S < 1) S = 1;
+    }
+    nitems = full + rem * S;
+  }
+  // item -> tile index and part (part < 0: the whole tile)
+  __device__ __forceinline__ void item(int it, int& l, int& part) const {
+    if (it < full || S == 1) {
+      l = c0 + it;
+      part = -1;
+    } else {
+      const int w = it - full;
+      l = c0 + full + w / S;
+      part = w - (w / S) * S;
+    }
   }
   // tile l -> expert e, packed rows [row0, row_end) (row0 + BM may exceed row_end), column n0
   __device__ __forceinline__ void locate(int l, int& e, int& row0, int& row_end, int& n0) const {

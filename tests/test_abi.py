@@ -58,6 +58,10 @@ def test_padded_ld_host_function():
 
 
 def test_workspace_sizes_and_desc_checks():
+    assert B.scmoe_expert_ffn_workspace_bytes(B.F32, 64, 256) == 0
+    assert B.scmoe_expert_ffn_workspace_bytes(B.BF16, 72, 40) == 0            # not an MFMA shape
+    nb = B.scmoe_expert_ffn_workspace_bytes(B.BF16, 2048, 8192)
+    assert nb >= 64 << 20 and nb % 16 == 0
     d = B.make_desc(256, 64, 256, 4, 1, 80, B.F32)
     n = B.scmoe_workspace_bytes(d)
     assert n % 256 == 0 and n >= 256 * 256 * 4 * 2
@@ -95,15 +99,17 @@ def test_argument_errors_launch_nothing():
     assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 3, 100, P, P, P, P, P, 64, P, 1 << 20, None) == 6
     assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 1, 100, None, P, P, P, P, 64, P, 1 << 20, None) == 1
     assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 1, -1, P, P, P, P, P, 64, P, 1 << 20, None) == 2
-    # expert ffn: (x, ld, dtype, offsets, max_rows, E, d, F, W1, ldw1, b1, W2, ldw2, b2, hidden, ldh, y, ldy, gelu, stream)
+    # expert ffn: (x, ld, dtype, offsets, max_rows, E, d, F, W1, ldw1, b1, W2, ldw2, b2, hidden, ldh, y, ldy, gelu,
+    #              workspace, ws_bytes, stream)
     ffn = lib.scmoe_expert_ffn
-    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 100, P, 64, None, P, 100, None, P, 100, P, 64, 0, None) == 2   # F % 8
-    assert ffn(P, 64, B.BF16, None, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 128, P, 64, 0, None) == 1
-    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 128, P, 64, 4, None) == 6
-    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 56, None, P, 128, None, P, 128, P, 64, 0, None) == 2   # ldw1 < d
-    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 132, None, P, 128, P, 64, 0, None) == 2   # ldw2 % 8
-    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 120, P, 64, 0, None) == 2   # ldh < F
-    assert ffn(None, 64, B.BF16, None, 0, 2, 64, 128, None, 64, None, None, 128, None, None, 128, None, 64, 0, None) == 0
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 100, P, 64, None, P, 100, None, P, 100, P, 64, 0, None, 0, None) == 2   # F % 8
+    assert ffn(P, 64, B.BF16, None, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 128, P, 64, 0, None, 0, None) == 1
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 128, P, 64, 4, None, 0, None) == 6
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 56, None, P, 128, None, P, 128, P, 64, 0, None, 0, None) == 2   # ldw1 < d
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 132, None, P, 128, P, 64, 0, None, 0, None) == 2   # ldw2 % 8
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 120, P, 64, 0, None, 0, None) == 2   # ldh < F
+    assert ffn(None, 64, B.BF16, None, 0, 2, 64, 128, None, 64, None, None, 128, None, None, 128, None, 64, 0, None, 0, None) == 0
+    assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 128, P, 64, 0, P + 8, 1 << 30, None) == 2  # workspace alignment
     # combine / coefficient gate
     assert lib.scmoe_combine(P, 64, B.F32, P, P, 10, 64, 3, None, 0, None, 0, None, P, 64, None) == 6
     assert lib.scmoe_combine(P, 64, B.F32, None, P, 10, 64, 1, None, 0, None, 0, None, P, 64, None) == 1

@@ -132,7 +132,8 @@ def test_dispatch_all_to_one_and_invalid(oracle):
 
 # ------------------------------------------------------------------------------- expert FFN
 
-def _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode, extra_rows=5, w_scale=0.05, pad=False):
+def _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode, extra_rows=5, w_scale=0.05, pad=False,
+              workspace=False):
     rng = np.random.default_rng(E * 100 + d + F)
     K = int(sum(lens))
     rows = K + extra_rows
@@ -149,8 +150,11 @@ def _ffn_case(oracle, E, lens, d, F, dtype, biases, gelu_mode, extra_rows=5, w_s
     ld1, ld2 = (B.scmoe_padded_ld(d, code), B.scmoe_padded_ld(F, code)) if pad else (d, F)
     hidden = torch.zeros((rows, ld2), dtype=gx.dtype, device=DEV)[:, :F]
     y = torch.full((rows, d), 7.0, dtype=gx.dtype, device=DEV)
+    ws = None
+    if workspace:
+        ws = torch.full((B.scmoe_expert_ffn_workspace_bytes(code, d, F),), 0x7f, dtype=torch.uint8, device=DEV)
     B.scmoe_expert_ffn(gx, torch.from_numpy(offsets).to(DEV), rows, to_dev(W1, dtype, ld1), to_dev(b1, "f32"),
-                       to_dev(W2, dtype, ld2), to_dev(b2, "f32"), hidden, y, gelu_mode=gelu_mode)
+                       to_dev(W2, dtype, ld2), to_dev(b2, "f32"), hidden, y, gelu_mode=gelu_mode, workspace=ws)
     torch.cuda.synchronize()
     g = to_host(y)
     assert (g[K:] == 7.0).all()                       # rows past offsets[E] are not touched
@@ -185,6 +189,23 @@ def test_expert_ffn_padded_row_strides(oracle, E, lens, d, F, dtype):
     g, _ = _ffn_case(oracle, E, lens, d, F, dtype, True, 0, pad=True)
     g0, _ = _ffn_case(oracle, E, lens, d, F, dtype, True, 0, pad=False)
     assert np.array_equal(g, g0)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_expert_ffn_split_k_tail(oracle, variant):
+    """With a workspace the last, partly filled round of tiles is cut along K (here: 3 tiles
+    left on one XCD, 1 on another).  Same bar; identical from run to run; the workspace may
+    hold anything on entry."""
+    B.scmoe_set_gemm_variant(variant)
+    try:
+        args = (oracle, 3, [1300, 200, 1500], 256, 1024, "bf16", True, 0)
+        g1, _ = _ffn_case(*args, workspace=True)
+        g2, _ = _ffn_case(*args, workspace=True)
+        g0, ref = _ffn_case(*args, workspace=False)
+        assert np.array_equal(g1, g2)
+        assert relerr(g1, g0) <= 1e-2
+    finally:
+        B.scmoe_set_gemm_variant(0)
 
 
 @pytest.mark.parametrize("variant", [0, 1, 2])
