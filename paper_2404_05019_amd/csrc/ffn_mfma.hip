@@ -33,7 +33,7 @@ struct TileCfg {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_;   // NS: LDS stages
   static constexpr int WAVES = WM * WN, THREADS = 64 * WAVES;
   static constexpr int TM = BM / WM, TN = BN / WN;       // wave tile
-  static constexpr int MI = TM / 32, NJ = TN / 32;       // 32x32 MFMA tiles per wave
+  static constexpr int MI = TM / 16, NJ = TN / 16;       // 16x16 MFMA tiles per wave
   static constexpr int RB = BK * 2;                      // bytes of one LDS row
   static constexpr int CPR = RB / 16;                    // 16-byte chunks per row
   static constexpr int RPL = 64 / CPR;                   // rows filled by one wave-wide load
@@ -47,7 +47,7 @@ struct TileCfg {
   static constexpr int WG_PER_CU = (160 * 1024 / LDS_BYTES) < (8 / WAVES) ? (160 * 1024 / LDS_BYTES) : (8 / WAVES);
   static constexpr int GM = 4;                           // row tiles per raster group
   static_assert(BM % (RPL * WAVES) == 0 && BN % (RPL * WAVES) == 0, "loads must divide evenly");
-  static_assert(TM % 32 == 0 && TN == 64 && (BK == 32 || BK == 64) && NS >= 2 && NS <= 4, "tile shape");
+  static_assert(TM == 128 && TN == 64 && (BK == 32 || BK == 64) && NS >= 2 && NS <= 4, "tile shape");
   static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024 && WG_PER_CU >= 1, "LDS budget");
 };
 
@@ -56,7 +56,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   constexpr int BM = CFG::BM, BN = CFG::BN, BK = CFG::BK, RB = CFG::RB, CPR = CFG::CPR;
   constexpr int MI = CFG::MI, NJ = CFG::NJ, STAGE = CFG::STAGE, A_BYTES = CFG::A_BYTES;
   constexpr int NS = CFG::NS;
-  constexpr int KS = BK / 16;                                   // k16-steps per k-tile (even)
+  constexpr int KS32 = BK / 32;                                 // 32-k MFMA steps per k-tile
+  constexpr int HS = 2 * KS32;                                  // half-steps per k-tile
   constexpr int LPW = CFG::A_PER_WAVE + CFG::B_PER_WAVE;        // direct loads per wave and k-tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -125,46 +126,67 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     else wait_vm(std::integral_constant<int, 0>{});
   };
 
-  // ---- fragment read offsets (the same for every tile) --------------------------------------
+  // ---- fragment reads (the same for every tile) ---------------------------------------------
+  // v_mfma_f32_16x16x32_bf16: an operand fragment is 16 rows x 32 k, lane l holding the 8
+  // consecutive k of chunk l / 16 of row l % 16.  (Per flop it moves half the accumulator
+  // data of the 32x32x16 form; with random operands a register-only loop of it sustains
+  // 2.09 PFLOP/s at 2.05 GHz against 1.78 PFLOP/s at 1.78 GHz: the chip is power-limited.)
+  // A wave's 128 x 64 tile is 8 x 4 such products per 32 k; it is walked in half-steps of
+  // 16 MFMAs: the 4 weight fragments of the 32 k against row-subtiles 0-3, then against 4-7.
   const int wave_m = wave / CFG::WN, wave_n = wave % CFG::WN;
-  const int lr = lane & 31, lh = lane >> 5;
-  // LDS byte address of (row, chunk lh) for k16-step 0 of stage 0, swizzled.  Kept as plain
-  // integers on top of an opaque base so that the address of any (stage, step, subtile) is
-  // one loop-invariant register plus an immediate: no address temporaries in the main loop
-  // that could alias fragment registers whose reads are still in flight.
+  const int l16 = lane & 15, lq = lane >> 4;
+  // LDS byte address of (row l16, chunk lq) for each 32-k step of stage 0, swizzled (the
+  // swizzle depends on row % 16 only).  Plain integers on top of an opaque base, so that the
+  // address of any (stage, step, subtile) is one loop-invariant register plus an immediate.
   unsigned lds0 = static_cast<unsigned>(reinterpret_cast<uintptr_t>(SCMOE_LDS_PTR(smem)));
   asm volatile("" : "+s"(lds0));
-  unsigned xoff[MI], woff[NJ];
+  unsigned xb[KS32], wb[KS32];
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    const int row = wave_m * CFG::TM + i * 32 + lr;
-    xoff[i] = lds0 + row * RB + ((lh ^ swz<CPR>(row)) << 4);
-  }
-#pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int row = wave_n * CFG::TN + j * 32 + lr;
-    woff[j] = lds0 + A_BYTES + row * RB + ((lh ^ swz<CPR>(row)) << 4);
+  for (int ks = 0; ks < KS32; ++ks) {
+    const unsigned cs = static_cast<unsigned>(((ks * 4 + lq) ^ swz<CPR>(l16)) << 4);
+    xb[ks] = lds0 + (wave_m * CFG::TM + l16) * RB + cs;
+    wb[ks] = lds0 + A_BYTES + (wave_n * CFG::TN + l16) * RB + cs;
   }
   typedef const __attribute__((address_space(3))) bf16x8_t* lds_frag_ptr;
 
-  f32x16_t acc[MI][NJ];
-  bf16x8_t xf[2][MI], wf[2][NJ];
-  auto load_frags = [&](int st, int s, int buf) {   // st: byte offset of the stage
-    // k16-step s reads chunks 2s and 2s+1: an XOR on the swizzled chunk index.  Read order =
-    // order of first use by the MFMAs (row-subtile major), so that the counter waits before
-    // the MFMAs of the next step can be partial.
+  f32x4_t acc[MI][NJ];          // MI = 8 row-subtiles, NJ = 4 column-subtiles of 16
+  bf16x8_t wf[2][NJ];           // weight fragments of a 32-k step, double-buffered: step q of stage R
+                                // uses buffer (R * KS32 + q) % 2, consecutive steps alternate
+  bf16x8_t xf[2][MI / 2];       // activation fragments of a half-step, one buffer per half
+  static_assert((NS * KS32) % 2 == 0, "the weight-fragment buffers alternate over the unrolled k loop");
+  // Reads for half-step hs of stage R.  Read order = order of first use.
+  auto load_frags = [&](int R, int hs) {
+    const int ks = hs >> 1, half = hs & 1, st = R * STAGE, wbuf = (R * KS32 + ks) & 1;
+    if (half == 0) {
 #pragma unroll
-    for (int t = 0; t < (MI > NJ ? MI : NJ); ++t) {
-      if (t < NJ) wf[buf][t] = *reinterpret_cast<lds_frag_ptr>(static_cast<uintptr_t>((woff[t] ^ (s << 5)) + st));
-      if (t < MI) xf[buf][t] = *reinterpret_cast<lds_frag_ptr>(static_cast<uintptr_t>((xoff[t] ^ (s << 5)) + st));
+      for (int t = 0; t < (MI / 2 > NJ ? MI / 2 : NJ); ++t) {
+        if (t < NJ) wf[wbuf][t] = *reinterpret_cast<lds_frag_ptr>(static_cast<uintptr_t>(wb[ks] + st + t * 16 * RB));
+        if (t < MI / 2) xf[0][t] = *reinterpret_cast<lds_frag_ptr>(static_cast<uintptr_t>(xb[ks] + st + t * 16 * RB));
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < MI / 2; ++t)
+        xf[1][t] = *reinterpret_cast<lds_frag_ptr>(static_cast<uintptr_t>(xb[ks] + st + (MI / 2 + t) * 16 * RB));
     }
   };
-  auto mfma_step = [&](int buf) {
+  auto mfma_step = [&](int R, int hs) {
+    const int ks = hs >> 1, half = hs & 1, wbuf = (R * KS32 + ks) & 1;
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < MI / 2; ++i)
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][j], xf[buf][i], acc[i][j], 0, 0, 0);
+        acc[half * (MI / 2) + i][j] =
+            __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[wbuf][j], xf[half][i], acc[half * (MI / 2) + i][j], 0, 0, 0);
+  };
+  // issue order of one half-step: MFMA, ds_read, MFMA, ds_read, ... (the reads feed the NEXT one)
+  auto interleave = [&](auto next_hs_c) {
+    constexpr int reads = (decltype(next_hs_c)::value & 1) ? MI / 2 : MI / 2 + NJ;
+#pragma unroll
+    for (int q = 0; q < reads; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, (MI / 2) * NJ - reads, 0);
   };
 
   int e, row0, row_end, n0, part;
@@ -188,16 +210,16 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
 
     // ---- main loop ---------------------------------------------------------------------------
-    // Global -> LDS runs NS-1 k-tiles ahead; LDS -> registers runs one k16-step ahead, each
+    // Global -> LDS runs NS-1 k-tiles ahead; LDS -> registers runs one half-step ahead, each
     // ds_read slotted behind an MFMA; one workgroup barrier per k-tile.  After an epilogue
     // the stores of the previous tile share the counter with the loads, so everything is
     // waited for (the prologue loads had the whole epilogue to land).
     wait_vm(std::integral_constant<int, 0>{});
     lds_barrier();
-    load_frags(0, 0, 0);
+    load_frags(0, 0);   // (stage 0, half-step 0)
     // One k-tile with its LDS stage known at compile time (the k loop is unrolled NS-fold),
     // so every LDS address is a loop-invariant register plus an immediate and no address
     // arithmetic has to share registers with fragments that are still in flight.
@@ -205,23 +227,13 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       constexpr int stage = decltype(stage_c)::value;
       constexpr bool steady = decltype(steady_c)::value;   // k-tiles kt+1 .. kt+NS all exist
       constexpr int next = (stage + 1 == NS) ? 0 : stage + 1;
-      constexpr int st = stage * STAGE;
-      // issue order of one step: MFMA, ds_read, MFMA, ds_read, ... (the reads feed the NEXT step)
-      auto interleave = [&]() {
-#pragma unroll
-        for (int q = 0; q < MI + NJ; ++q) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, MI * NJ - (MI + NJ), 0);
-      };
-#pragma unroll
-      for (int s = 0; s + 1 < KS; ++s) {
+      static_for<0, HS - 1>([&](auto hs_c) {
+        constexpr int hs = decltype(hs_c)::value;
         __builtin_amdgcn_sched_barrier(0);
-        load_frags(st, s + 1, (s + 1) & 1);
-        mfma_step(s & 1);
-        interleave();
-      }
+        load_frags(stage, hs + 1);
+        mfma_step(stage, hs);
+        interleave(std::integral_constant<int, hs + 1>{});
+      });
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (steady) {
         // No branches here: the compiler's counter bookkeeping merges conservatively at every
@@ -231,9 +243,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
         lds_barrier();
         issue_loads(kt + NS, stage);
         __builtin_amdgcn_sched_barrier(0);
-        load_frags(next * STAGE, 0, 0);
-        mfma_step((KS - 1) & 1);
-        interleave();
+        load_frags(next, 0);
+        mfma_step(stage, HS - 1);
+        interleave(std::integral_constant<int, 0>{});
       } else {
         if (kt + 1 < nk) {
           // k-tiles kt+1 .. min(kt+NS-1, nk-1) are in flight; k-tile kt+1 must have landed.
@@ -243,10 +255,10 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
           wait_tiles(later < NS - 2 ? later : NS - 2);
           lds_barrier();
           if (kt + NS < nk) issue_loads(kt + NS, stage);
-          load_frags(next * STAGE, 0, 0);
+          load_frags(next, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-        mfma_step((KS - 1) & 1);
+        mfma_step(stage, HS - 1);
       }
     };
     using std::integral_constant;
@@ -289,20 +301,15 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     bool finish = true;
     if (cpart >= 0) {
       constexpr int TILE = BM * BN;
-      constexpr int FRAGS = MI * NJ * 4;                              // 16-byte pieces per lane
+      constexpr int FRAGS = MI * NJ;                                  // 16-byte pieces (accumulators) per lane
       const int S = sched.S;
       const size_t slot0 = static_cast<size_t>(sched.xcd) * nslots;   // this XCD's scratch slots
-      // piece (i, j, g) of wave w and lane l sits at float4 index ((w * FRAGS + (i*NJ+j)*4 + g) * 64 + l
+      // accumulator (i, j) of wave w and lane l sits at float4 index (w * FRAGS + i * NJ + j) * 64 + l
       float* mine = p.splitk_part + (slot0 + cw) * TILE + ((wave * FRAGS) * 64 + lane) * 4;
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4_t v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-            store16_device_scope(mine + (((i * NJ + j) * 4 + g) * 64) * 4, v);
-          }
+        for (int j = 0; j < NJ; ++j) store16_device_scope(mine + ((i * NJ + j) * 64) * 4, acc[i][j]);
       wait_vm(std::integral_constant<int, 0>{});                      // this wave's stores have been performed
       lds_barrier();
       int* flag = reinterpret_cast<int*>(smem + NS * STAGE);          // first word of wave 0's epilogue patch
@@ -322,49 +329,48 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
         for (int q = 0; q < S; ++q) {
           const float* src = first + static_cast<size_t>(q) * TILE;
 #pragma unroll
-          for (int i = 0; i < MI; ++i)
+          for (int i = 0; i < MI; ++i) {
+            f32x4_t t[NJ];
+            static_assert(NJ == 4, "four pieces 1 KiB apart per load group");
+            load4x16_device_scope(src + ((i * NJ) * 64) * 4, t[0], t[1], t[2], t[3]);
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-              f32x4_t t[4];
-              load4x16_device_scope(src + (((i * NJ + j) * 4) * 64) * 4, t[0], t[1], t[2], t[3]);
-#pragma unroll
-              for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                  acc[i][j][4 * g + c] = (q == 0) ? t[g][c] : acc[i][j][4 * g + c] + t[g][c];
-            }
+            for (int j = 0; j < NJ; ++j) acc[i][j] = (q == 0) ? t[j] : acc[i][j] + t[j];
+          }
         }
       }
     }
 
     // ---- epilogue: bias, activation, bf16; rows re-assembled in LDS, 16-byte stores ---------
-    // acc[i][j][v] is output row (lane & 31) of row-subtile i and column
-    // 8*(v/4) + 4*(lane/32) + v%4 of column-subtile j.  A wave stages one 32-row slab of its
-    // tile in its private LDS patch and writes it out with TN/8 lanes per row, so that every
-    // store instruction covers whole 128-byte lines.
+    // acc[i][j][v] is output row (lane % 16) of row-subtile i and column 4 * (lane / 16) + v of
+    // column-subtile j.  A wave stages 32-row slabs (two row-subtiles) of its tile in its
+    // private LDS patch and writes them out with TN/8 lanes per row, so that every store
+    // instruction covers whole 128-byte lines.
     const float* bias_e = p.bias ? p.bias + static_cast<int64_t>(ce) * p.N : nullptr;
     unsigned char* stg = smem + NS * STAGE + wave * CFG::STG_BYTES;
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+    for (int i = 0; i < MI / 2; ++i) {
       const int mbase = crow0 + wave_m * CFG::TM + i * 32;
       if (!finish || mbase >= crow_end) continue;   // wave-uniform: not the last part / slab past the segment
-      float rscale = 1.0f;                      // fused decode: the gate weight of this lane's row
+      float rscale[2] = {1.0f, 1.0f};             // fused decode: the gate weights of this lane's two rows
       if (p.scatter) {
-        const int mr = (mbase + lr < crow_end) ? mbase + lr : crow_end - 1;
-        rscale = p.row_scale[p.scatter[mr]];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int mr = (mbase + u * 16 + l16 < crow_end) ? mbase + u * 16 + l16 : crow_end - 1;
+          rscale[u] = p.row_scale[p.scatter[mr]];
+        }
       }
 #pragma unroll
       for (int h = 0; h < 32 / CFG::STG_ROWS; ++h) {
-        const int sr = lr - h * CFG::STG_ROWS;  // this lane's row inside the staged rows
-        const bool mine = sr >= 0 && sr < CFG::STG_ROWS;
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
+        for (int u = 0; u < 2; ++u) {
+          const int sr = u * 16 + l16 - h * CFG::STG_ROWS;   // this lane's row inside the staged rows
+          const bool mine = sr >= 0 && sr < CFG::STG_ROWS;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int n = cn0 + wave_n * CFG::TN + j * 32 + 8 * g + 4 * lh;
+          for (int j = 0; j < NJ; ++j) {
+            const int n = cn0 + wave_n * CFG::TN + j * 16 + 4 * lq;
             float v[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] = acc[i][j][4 * g + q];
+            for (int q = 0; q < 4; ++q) v[q] = acc[2 * i + u][j][q];
             if (bias_e && n < p.N) {
               const float4 b = *reinterpret_cast<const float4*>(bias_e + n);
               v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
@@ -376,13 +382,15 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
             }
             if (p.scatter) {
 #pragma unroll
-              for (int q = 0; q < 4; ++q) v[q] *= rscale;
+              for (int q = 0; q < 4; ++q) v[q] *= rscale[u];
             }
             uint2 o;
             o.x = cvt_pk_bf16(v[0], v[1]);
             o.y = cvt_pk_bf16(v[2], v[3]);
-            // 16-byte chunk 4j+g of the row, swizzled like the operand tiles; half lh of it
-            if (mine) *reinterpret_cast<uint2*>(stg + sr * CFG::STG_ROW + (((4 * j + g) ^ swz<8>(sr)) << 4) + lh * 8) = o;
+            // columns 16 j + 4 lq ...: 16-byte chunk 2j + lq/2 of the row (swizzled like the
+            // operand tiles), half lq % 2 of it
+            if (mine)
+              *reinterpret_cast<uint2*>(stg + sr * CFG::STG_ROW + (((2 * j + (lq >> 1)) ^ swz<8>(sr)) << 4) + (lq & 1) * 8) = o;
           }
         }
 #pragma unroll
@@ -417,11 +425,10 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 
 using CfgA = TileCfg<256, 256, 64, 2, 4, 2>;   // 8 waves, 128 KiB LDS, one workgroup per CU
 using CfgB = TileCfg<256, 256, 32, 2, 4, 4>;   // 8 waves, 4 stages, 128 KiB LDS
-using CfgC = TileCfg<256, 128, 32, 2, 2, 3>;   // 4 waves, 3 stages, 72 KiB LDS, two workgroups per CU
 
 // Tile configuration in use: set by scmoe_set_gemm_variant, else SCMOE_GEMM_VARIANT, else 0.
 static int g_variant = -1;
-constexpr int NUM_VARIANTS = 3;
+constexpr int NUM_VARIANTS = 2;
 
 static int gemm_variant() {
   if (g_variant < 0) {
@@ -470,7 +477,6 @@ template <bool ACT>
 static int launch_variant(const GemmArgs& a, int max_rows, hipStream_t stream) {
   switch (gemm_variant()) {
     case 1: return launch_gemm<CfgB, ACT>(a, max_rows, stream);
-    case 2: return launch_gemm<CfgC, ACT>(a, max_rows, stream);
     default: return launch_gemm<CfgA, ACT>(a, max_rows, stream);
   }
 }

@@ -191,7 +191,7 @@ def test_expert_ffn_padded_row_strides(oracle, E, lens, d, F, dtype):
     assert np.array_equal(g, g0)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1])
 def test_expert_ffn_split_k_tail(oracle, variant):
     """With a workspace the last, partly filled round of tiles is cut along K (here: 3 tiles
     left on one XCD, 1 on another).  Same bar; identical from run to run; the workspace may
@@ -208,7 +208,7 @@ def test_expert_ffn_split_k_tail(oracle, variant):
         B.scmoe_set_gemm_variant(0)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1])
 def test_expert_ffn_tile_variants(oracle, variant):
     """Every tile configuration of the MFMA grouped GEMM meets the same bar."""
     B.scmoe_set_gemm_variant(variant)
