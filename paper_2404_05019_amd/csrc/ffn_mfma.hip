@@ -4,26 +4,28 @@
 //   C[r, n] = act( sum_k A[row(r), k] * W[e, n, k] + bias[e, n] ),  r in segment e
 //
 // Both operands are K-contiguous ([rows, K] activations, [N, K] weights), which is the
-// layout v_mfma_f32_32x32x16_bf16 wants: each lane feeds 8 consecutive k of one row.
+// layout v_mfma_f32_16x16x32_bf16 wants: each lane feeds 8 consecutive k of one row.
 //
 // Design (gfx950):
 //  * Persistent workgroups; each takes BM x BN output tiles (one expert per tile) from a
 //    schedule derived on the device from offsets[] (no host round trip), and requests the
-//    first k-tiles of its next tile before it runs the epilogue of the current one.
+//    first k-tiles of its next tile before it runs the epilogue of the current one.  The
+//    tiles of the last, partly filled round are cut along K (see the split-K block below).
 //  * Global -> LDS copies use the direct-to-LDS form of the global load (16 bytes per
 //    lane, no VGPR staging).  Such a load writes 1 KiB of consecutive LDS per wave, so the
 //    bank-conflict swizzle is applied on the global side: the lane that fills LDS slot
 //    (row, c) fetches k-chunk  c ^ swz(row)  of that row.
 //  * N LDS stages and double-buffered register fragments: global loads run N-1 k-tiles
-//    ahead, LDS reads one k16-step ahead, issued one behind each MFMA; one workgroup
-//    barrier per k-tile.
+//    ahead, LDS reads one half-step (16 MFMAs) ahead, issued one behind each MFMA; one
+//    workgroup barrier per k-tile, which orders LDS traffic only (lds_barrier).
 //  * The MFMA is issued with the weight fragment as its first operand, so a lane ends up
 //    holding 4 consecutive output columns of one row; the epilogue re-assembles rows in a
 //    small per-wave LDS patch and stores whole 128-byte lines.
 //  * Workgroup ids are remapped so that each XCD (ids congruent mod 8 land on one XCD and
 //    share its L2) walks a compact block of neighbouring tiles.
-//  * Rows can be gathered on load through an index array (the dispatch permutation), which
-//    lets the layer skip materialising the permuted activations.
+//  * Rows can be gathered on load through an index array (the dispatch permutation, paper
+//    Sec. 2.2 "input encode"), and the second GEMM can scatter, scale and add on store
+//    ("output decode"), which lets the layer skip both permuted copies.
 #include "mfma_common.hpp"
 
 namespace scmoe {
