@@ -207,12 +207,19 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   setup(it);
   issue_prologue();
   for (;;) {
+    // The accumulators start from the bias (lane: columns 16 j + 4 lq ... of its column block;
+    // for a split-K item only in part 0).  Loading it here and not in the epilogue matters:
+    // a load in the epilogue would wait behind the next tile's first k-tiles, which are
+    // requested before the epilogue and complete in issue order.
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int j = 0; j < NJ; ++j) {
+      const int n = n0 + wave_n * CFG::TN + j * 16 + 4 * lq;
+      f32x4_t b = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (p.bias != nullptr && part <= 0 && n < p.N)
+        b = *reinterpret_cast<const f32x4_t*>(p.bias + static_cast<int64_t>(e) * p.N + n);
 #pragma unroll
-      for (int j = 0; j < NJ; ++j)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
+      for (int i = 0; i < MI; ++i) acc[i][j] = b;
+    }
 
     // ---- main loop ---------------------------------------------------------------------------
     // Global -> LDS runs NS-1 k-tiles ahead; LDS -> registers runs one half-step ahead, each
@@ -286,7 +293,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     // ---- next tile: its first k-tiles are requested before this tile's epilogue -----------
     const int itn = it + nslots;
     const bool more = itn < sched.nitems;
-    const int ce = e, crow0 = row0, crow_end = row_end, cn0 = n0, cpart = part, cw = it - sched.full;
+    const int crow0 = row0, crow_end = row_end, cn0 = n0, cpart = part, cw = it - sched.full;
     lds_barrier();                    // every wave holds its last fragments: LDS is free
     if (more) {
       setup(itn);
@@ -342,12 +349,11 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       }
     }
 
-    // ---- epilogue: bias, activation, bf16; rows re-assembled in LDS, 16-byte stores ---------
+    // ---- epilogue: activation, bf16; rows re-assembled in LDS, 16-byte stores ----------------
     // acc[i][j][v] is output row (lane % 16) of row-subtile i and column 4 * (lane / 16) + v of
     // column-subtile j.  A wave stages 32-row slabs (two row-subtiles) of its tile in its
     // private LDS patch and writes them out with TN/8 lanes per row, so that every store
     // instruction covers whole 128-byte lines.
-    const float* bias_e = p.bias ? p.bias + static_cast<int64_t>(ce) * p.N : nullptr;
     unsigned char* stg = smem + NS * STAGE + wave * CFG::STG_BYTES;
 #pragma unroll
     for (int i = 0; i < MI / 2; ++i) {
@@ -369,14 +375,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
           const bool mine = sr >= 0 && sr < CFG::STG_ROWS;
 #pragma unroll
           for (int j = 0; j < NJ; ++j) {
-            const int n = cn0 + wave_n * CFG::TN + j * 16 + 4 * lq;
             float v[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) v[q] = acc[2 * i + u][j][q];
-            if (bias_e && n < p.N) {
-              const float4 b = *reinterpret_cast<const float4*>(bias_e + n);
-              v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
-            }
             if (ACT) {
 #pragma unroll
               for (int q = 0; q < 4; ++q)
