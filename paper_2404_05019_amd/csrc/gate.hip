@@ -6,9 +6,12 @@
 // finds its parallelism elsewhere: a workgroup owns 64 tokens, lane = token, and each of
 // its four waves owns a contiguous group of EPL experts, so every lane runs EPL independent
 // FMA chains.  x is staged through LDS in [64 tokens x 256 bytes] tiles (coalesced HBM
-// reads although each lane walks its own row; the next tile is prefetched into registers
-// while the current one is consumed), and so is the matching slab of W_g, which all lanes
-// of a wave then read at one address (an LDS broadcast).
+// reads although each lane walks its own row), and so is the matching slab of W_g, which all
+// lanes of a wave then read at one address (an LDS broadcast); the next tile of both is
+// prefetched into registers while the current one is consumed.  Tried without gain: W_g
+// through the scalar cache into SGPRs (3x slower: one scalar load per feature and wave) and
+// one W read per 16 features with a DPP row broadcast inside the FMA (same time: LDS traffic
+// is not what bounds the kernel).
 #include "common.hpp"
 
 namespace scmoe {
@@ -61,7 +64,26 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_kernel(
       if (((tid + u * GATE_THREADS) & 15) < nvec)
         pre[u] = *reinterpret_cast<const uint4*>(src[u] + static_cast<int64_t>(kc0) * EB);
   };
+  // this thread's pieces of the W_g slab of a tile: KC x EPAD floats, WV float4 pieces each
+  constexpr int WV = (KC * EPAD / 4 + GATE_THREADS - 1) / GATE_THREADS;
+  float4 wpre[WV];
+  auto fetch_w = [&](int kc0) {
+    const int kn = (d - kc0 < KC) ? d - kc0 : KC;
+#pragma unroll
+    for (int u = 0; u < WV; ++u) {
+      const int c = (tid + u * GATE_THREADS) * 4;          // first of four expert columns
+      const int i = c / EPAD, e = c - i * EPAD;
+      float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (i < kn) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (e + q < E) w[q] = Wg[static_cast<int64_t>(kc0 + i) * E + e + q];
+      }
+      wpre[u] = make_float4(w[0], w[1], w[2], w[3]);
+    }
+  };
   fetch(0);
+  fetch_w(0);
 
   for (int kc0 = 0; kc0 < d; kc0 += KC) {
     const int kn = (d - kc0 < KC) ? d - kc0 : KC;  // features in this tile (multiple of 8)
@@ -72,12 +94,16 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_kernel(
       const int c = tid + u * GATE_THREADS;
       if ((c & 15) < nvec) *reinterpret_cast<uint4*>(xs + (c >> 4) * GATE_ROW_STRIDE + (c & 15) * 16) = pre[u];
     }
-    for (int c = tid; c < kn * EPAD; c += GATE_THREADS) {
-      const int i = c / EPAD, e = c - i * EPAD;
-      ws[c] = (e < E) ? Wg[static_cast<int64_t>(kc0 + i) * E + e] : 0.0f;
+#pragma unroll
+    for (int u = 0; u < WV; ++u) {
+      const int c = (tid + u * GATE_THREADS) * 4;
+      if (c < KC * EPAD) *reinterpret_cast<float4*>(ws + c) = wpre[u];
     }
     __syncthreads();
-    if (kc0 + KC < d) fetch(kc0 + KC);             // in flight while this tile is consumed
+    if (kc0 + KC < d) {                            // in flight while this tile is consumed
+      fetch(kc0 + KC);
+      fetch_w(kc0 + KC);
+    }
     if (e0 < E) {
       const unsigned char* myrow = xs + lane * GATE_ROW_STRIDE;
       constexpr int XPV = 16 / EB;                 // features per 16-byte piece
