@@ -70,6 +70,7 @@ struct FfnArgs {
   const void* x; int64_t ldx;      // [rows, d] activations
   const int32_t* gather;           // row r reads x[gather[r]] (the dispatch permutation applied
                                    // on load); nullptr = identity.  MFMA path only.
+  int64_t x_rows;                  // with gather: rows of x that gather may name
   const int32_t* offsets;          // [E + 1] segment starts, device
   int max_rows, E, d, F;
   const void* W1; int64_t ldw1; const float* b1;   // [E, F, d]

@@ -53,7 +53,7 @@ struct TileCfg {
   static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024 && WG_PER_CU >= 1, "LDS budget");
 };
 
-template <class CFG, bool ACT>
+template <class CFG, bool ACT, bool OFF32>
 __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void gemm_bf16_kernel(const GemmArgs p) {
   constexpr int BM = CFG::BM, BN = CFG::BN, BK = CFG::BK, RB = CFG::RB, CPR = CFG::CPR;
   constexpr int MI = CFG::MI, NJ = CFG::NJ, STAGE = CFG::STAGE, A_BYTES = CFG::A_BYTES;
@@ -76,10 +76,19 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   int nk = nk_all;                         // k-tiles of the current item
 
   // ---- per-lane source addresses of the direct-to-LDS loads -------------------------------
-  const unsigned char* aptr[CFG::A_PER_WAVE];
-  const unsigned char* bptr[CFG::B_PER_WAVE];
+  // OFF32 (both operands span less than 4 GiB, checked on the host): an address is a
+  // wave-uniform 64-bit base plus a 32-bit per-lane offset, which the load takes as scalar
+  // base + vector offset: one register per load and no vector address arithmetic between
+  // the barrier of a k-tile and its next MFMA.  Otherwise full 64-bit per-lane pointers.
+  const unsigned char* aptr[OFF32 ? 1 : CFG::A_PER_WAVE];
+  const unsigned char* bptr[OFF32 ? 1 : CFG::B_PER_WAVE];
+  uint32_t aoff[OFF32 ? CFG::A_PER_WAVE : 1], boff[OFF32 ? CFG::B_PER_WAVE : 1];
+  const unsigned char* abase = nullptr;     // OFF32: p.A / the expert's W, advanced to the item's first k-tile
+  const unsigned char* wbase = nullptr;
   auto set_ptrs = [&](int e, int row0, int row_end, int n0, int kb) {   // kb: first k-tile of the item
     const unsigned char* We = p.W + static_cast<int64_t>(e) * p.N * p.ldw * 2 + static_cast<int64_t>(kb) * RB;
+    abase = p.A + static_cast<int64_t>(kb) * RB;
+    wbase = We;
 #pragma unroll
     for (int i = 0; i < CFG::A_PER_WAVE; ++i) {
       const int row = (wave * CFG::A_PER_WAVE + i) * CFG::RPL + lane / CPR;
@@ -87,7 +96,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       int m = row0 + row;
       if (m > row_end - 1) m = row_end - 1;      // rows past the segment re-read its last row
       const int64_t src = p.gather ? p.gather[m] : m;
-      aptr[i] = p.A + src * p.lda * 2 + kc * 16 + static_cast<int64_t>(kb) * RB;
+      if constexpr (OFF32) aoff[i] = static_cast<uint32_t>(src * p.lda * 2 + kc * 16);
+      else aptr[i] = abase + src * p.lda * 2 + kc * 16;
     }
 #pragma unroll
     for (int i = 0; i < CFG::B_PER_WAVE; ++i) {
@@ -95,20 +105,36 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       const int kc = (lane % CPR) ^ swz<CPR>(row);
       int n = n0 + row;
       if (n > p.N - 1) n = p.N - 1;
-      bptr[i] = We + static_cast<int64_t>(n) * p.ldw * 2 + kc * 16;
+      if constexpr (OFF32) boff[i] = static_cast<uint32_t>(static_cast<int64_t>(n) * p.ldw * 2 + kc * 16);
+      else bptr[i] = We + static_cast<int64_t>(n) * p.ldw * 2 + kc * 16;
     }
   };
   auto issue_loads = [&](int kt, int stage) {
     unsigned char* sa = smem + stage * STAGE + wave * CFG::A_PER_WAVE * 1024;
     unsigned char* sb = smem + stage * STAGE + A_BYTES + wave * CFG::B_PER_WAVE * 1024;
+    const unsigned char* ak = abase + static_cast<int64_t>(kt) * RB;
+    const unsigned char* wk = wbase + static_cast<int64_t>(kt) * RB;
+    if constexpr (OFF32) asm volatile("" : "+s"(ak), "+s"(wk));   // the scalar sums stay scalar
 #pragma unroll
-    for (int i = 0; i < CFG::A_PER_WAVE; ++i)
-      __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(aptr[i] + static_cast<int64_t>(kt) * RB),
-                                       SCMOE_LDS_PTR(sa + i * 1024), 16, 0, 0);
+    for (int i = 0; i < CFG::A_PER_WAVE; ++i) {
+      if constexpr (OFF32) {
+        asm volatile("" : "+v"(aoff[i]));   // keeps the offset a 32-bit register of its own
+        __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(ak + aoff[i]), SCMOE_LDS_PTR(sa + i * 1024), 16, 0, 0);
+      } else {
+        __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(aptr[i] + static_cast<int64_t>(kt) * RB),
+                                         SCMOE_LDS_PTR(sa + i * 1024), 16, 0, 0);
+      }
+    }
 #pragma unroll
-    for (int i = 0; i < CFG::B_PER_WAVE; ++i)
-      __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(bptr[i] + static_cast<int64_t>(kt) * RB),
-                                       SCMOE_LDS_PTR(sb + i * 1024), 16, 0, 0);
+    for (int i = 0; i < CFG::B_PER_WAVE; ++i) {
+      if constexpr (OFF32) {
+        asm volatile("" : "+v"(boff[i]));
+        __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(wk + boff[i]), SCMOE_LDS_PTR(sb + i * 1024), 16, 0, 0);
+      } else {
+        __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(bptr[i] + static_cast<int64_t>(kt) * RB),
+                                         SCMOE_LDS_PTR(sb + i * 1024), 16, 0, 0);
+      }
+    }
   };
   auto issue_prologue = [&]() {
 #pragma unroll
@@ -450,11 +476,11 @@ int set_gemm_variant(int v) {
 
 bool ffn_mfma_supported(int d, int F) { return d > 0 && F > 0 && (d % 64) == 0 && (F % 64) == 0; }
 
-template <class CFG, bool ACT>
-static int launch_gemm(GemmArgs a, int max_rows, hipStream_t stream) {
+template <class CFG, bool ACT, bool OFF32>
+static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<CFG, ACT>),
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<CFG, ACT, OFF32>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, CFG::LDS_BYTES);
     if (err != hipSuccess) return hip_fail(err);
     attr_set = true;
@@ -471,16 +497,25 @@ static int launch_gemm(GemmArgs a, int max_rows, hipStream_t stream) {
     a.splitk_part = nullptr;
     a.splitk_count = nullptr;
   }
-  hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT>), dim3(8 * slots), dim3(CFG::THREADS), CFG::LDS_BYTES,
+  hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT, OFF32>), dim3(8 * slots), dim3(CFG::THREADS), CFG::LDS_BYTES,
                      stream, a);
   return launch_status();
 }
 
+// a_rows: rows of the activation matrix that can be addressed (through `gather` any of them).
+template <class CFG, bool ACT>
+static int launch_gemm(const GemmArgs& a, int max_rows, int64_t a_rows, hipStream_t stream) {
+  const int64_t lim = int64_t(1) << 32;
+  const bool off32 = a_rows * a.lda * 2 < lim && static_cast<int64_t>(a.N) * a.ldw * 2 < lim;
+  return off32 ? launch_gemm_impl<CFG, ACT, true>(a, max_rows, stream)
+               : launch_gemm_impl<CFG, ACT, false>(a, max_rows, stream);
+}
+
 template <bool ACT>
-static int launch_variant(const GemmArgs& a, int max_rows, hipStream_t stream) {
+static int launch_variant(const GemmArgs& a, int max_rows, int64_t a_rows, hipStream_t stream) {
   switch (gemm_variant()) {
-    case 1: return launch_gemm<CfgB, ACT>(a, max_rows, stream);
-    default: return launch_gemm<CfgA, ACT>(a, max_rows, stream);
+    case 1: return launch_gemm<CfgB, ACT>(a, max_rows, a_rows, stream);
+    default: return launch_gemm<CfgA, ACT>(a, max_rows, a_rows, stream);
   }
 }
 
@@ -519,7 +554,7 @@ int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   g1.gelu_mode = a.gelu_mode;
   g1.splitk_part = parts;
   g1.splitk_count = counters;
-  int st = launch_variant<true>(g1, a.max_rows, stream);
+  int st = launch_variant<true>(g1, a.max_rows, a.gather ? a.x_rows : a.max_rows, stream);
   if (st != SCMOE_OK) return st;
   GemmArgs g2{};
   g2.A = static_cast<const unsigned char*>(a.hidden);
@@ -541,7 +576,7 @@ int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   g2.ldadd = a.ldadd;
   g2.splitk_part = parts;
   g2.splitk_count = counters;
-  return launch_variant<false>(g2, a.max_rows, stream);
+  return launch_variant<false>(g2, a.max_rows, a.max_rows, stream);
 }
 
 }  // namespace scmoe

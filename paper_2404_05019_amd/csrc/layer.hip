@@ -178,6 +178,7 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
   a.x = gol ? x : w.x_perm;
   a.ldx = gol ? ldx : D->d;
   a.gather = gol ? w.src_token : nullptr;
+  a.x_rows = D->T;
   a.offsets = w.offsets;
   a.max_rows = rows; a.E = D->E; a.d = D->d; a.F = D->F;
   a.W1 = W->W1; a.ldw1 = ld_or(W->ld_w1, D->d); a.b1 = W->b1;
