@@ -33,6 +33,10 @@ def parse():
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="1: all kernels in order on one stream; 2: shared expert on a second stream")
     ap.add_argument("--gemm-variant", type=int, default=None)
+    ap.add_argument("--offload", type=int, default=0, metavar="T",
+                    help="instead of the throughput bench: latency of one block for a decode-like batch of T "
+                         "tokens (widths and experts of --workload) with the routed experts resident, offloaded "
+                         "with blocking migration, and offloaded with asynchronous migration")
     ap.add_argument("--no-ffn-workspace", action="store_true",
                     help="time the scmoe_expert_ffn leg without its optional scratch (no split-K of the last round)")
     ap.add_argument("--padded-weights", action="store_true",
@@ -59,6 +63,57 @@ def time_region(torch, fn, steps, warmup):
     return e0.elapsed_time(e1) / steps
 
 
+def offload_bench(args):
+    """Expert offloading (Sec. 5.3 / appendix A.3 of the paper) on a decode-like batch."""
+    import torch
+    from paper_2404_05019_amd import binding as B
+    from paper_2404_05019_amd import inputs
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import DEV, DevLayer
+    cfg = inputs.CONFIGS[args.workload]
+    T, d, F, E = args.offload, cfg["d"], cfg["F"], cfg["E"]
+    L = inputs.make_layer(T=T, d=d, F=F, E=E, dtype="bf16", seed=cfg.get("seed", 5) + 100, biases=True)
+    D = DevLayer(L, "bf16")
+    desc = B.make_desc(T, d, F, E, 1, T, D.code)
+    ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    y = torch.empty((T, d), dtype=D.tdtype, device=DEV)
+    host = lambda t: None if t is None else t.cpu().pin_memory()
+    wts = B.make_weights(D.Wg, host(D.W1), host(D.W2), D.W1s, D.W2s, D.bias, host(D.b1), host(D.b2), D.b1s, D.b2s,
+                         D.Wcg)
+    n_pool = min(E, T)
+    pool = torch.empty(B.scmoe_offload_pool_bytes(desc, n_pool), dtype=torch.uint8, device=DEV)
+    plan = torch.zeros(2 * E + 1, dtype=torch.int32).pin_memory()
+    cs = torch.cuda.Stream()
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms_res = timed(lambda: B.scmoe_layer_forward(desc, D.x_prev, D.x_cur, D.weights, y, ws))
+    ms_blk = timed(lambda: B.scmoe_layer_forward_offload(desc, D.x_prev, D.x_cur, wts, pool, n_pool, plan, y, ws,
+                                                         async_copy=False))
+    ms_asy = timed(lambda: B.scmoe_layer_forward_offload(desc, D.x_prev, D.x_cur, wts, pool, n_pool, plan, y, ws,
+                                                         async_copy=True, stream_copy=cs))
+    active = int((plan[:E] > 0).sum())
+    expert_bytes = 2 * d * F * 2 + (d + F) * 4
+    print(json.dumps({
+        "metric": "ScMoE block latency with expert offloading (1 MI355X)", "value": round(ms_asy, 4), "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload + " widths, decode batch", "T": T, "d_model": d, "d_ffn": F, "E": E,
+                   "top_k": 1, "experts_selected": active, "pool_experts": n_pool},
+        "resident_ms": round(ms_res, 4), "offload_blocking_ms": round(ms_blk, 4), "offload_async_ms": round(ms_asy, 4),
+        "migrated_bytes_per_step": active * expert_bytes,
+        "routed_expert_bytes_resident": E * expert_bytes, "pool_bytes": pool.numel(),
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -75,6 +130,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.gemm_variant is not None:
         B.scmoe_set_gemm_variant(args.gemm_variant)
+    if args.offload > 0:
+        offload_bench(args)
+        return
 
     t_gen = time.time()
     L, cfg = inputs.make_config(args.workload)

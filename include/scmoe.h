@@ -279,6 +279,38 @@ int scmoe_layer_forward(const scmoe_desc* desc, const void* x_prev, int64_t ld_p
                         const scmoe_routing_out* routing, void* workspace, size_t ws_bytes,
                         void* stream_main, void* stream_aux);
 
+/* Bytes of the device pool that receives migrated experts: room for `pool_experts` experts
+ * (W1, W2, b1, b2 of each).  `desc`, `out`: host pointers. */
+int scmoe_offload_pool_bytes(const scmoe_desc* desc, int32_t pool_experts, size_t* out);
+
+/*
+ * ScMoE block forward with the gate-routed experts offloaded to host memory and migrated on
+ * demand (Sec. 5.3 "expert offloading", appendix A.3): the shared expert and the gate stay
+ * on the GPU; because ScMoE selects experts from the preceding-layer representation, the
+ * selection is known before the current layer's computation starts, and exactly the selected
+ * experts are copied host -> device (determinate migration, nothing is predicted) while the
+ * shared expert runs.
+ *
+ *   w->W1, w->W2, w->b1, w->b2   HOST pointers ([E,F,d], [E,d,F], [E,F], [E,d]; dense;
+ *                                pinned memory is needed for the copies to overlap);
+ *   all other members of w       device pointers as in scmoe_layer_forward;
+ *   expert_pool                  device, 256-byte aligned, scmoe_offload_pool_bytes bytes;
+ *   host_plan                    host scratch of 2*E + 1 int32 (pinned recommended); on return
+ *                                [0, E) holds the kept rows per expert;
+ *   async_copy                   1: copies on stream_copy, overlapped with the shared expert
+ *                                ("Offload-Async"); 0: copies on stream_main in front of the
+ *                                shared expert ("Offload", blocking migration).
+ *
+ * The call synchronises stream_main once on the host (the host reads the per-expert counts to
+ * issue the copies).  SCMOE_ERR_WORKSPACE if more experts are selected than the pool holds.
+ * Result: identical, bit for bit, to scmoe_layer_forward's combine path on the same inputs.
+ */
+int scmoe_layer_forward_offload(const scmoe_desc* desc, const void* x_prev, int64_t ld_prev,
+                                const void* x_cur, int64_t ld_cur, const scmoe_weights* w,
+                                void* expert_pool, int32_t pool_experts, int32_t async_copy,
+                                int32_t* host_plan, void* y, int64_t ldy, void* workspace,
+                                size_t ws_bytes, void* stream_main, void* stream_copy);
+
 /*
  * Standard top-k MoE layer on the current-layer representation (Eq. (1)-(4); k = 2 is the
  * baseline the paper compares with, Fig. 2(a)):  y = sum_j gate_w[t,j] E_{idx[t,j]}(x[t]).

@@ -22,7 +22,8 @@ EXPORTS = ["scmoe_status_string", "scmoe_last_hip_error", "scmoe_set_gemm_varian
            "scmoe_gate_top2", "scmoe_dispatch_workspace_bytes", "scmoe_dispatch", "scmoe_expert_ffn",
            "scmoe_expert_ffn_workspace_bytes",
            "scmoe_combine", "scmoe_coef_gate", "scmoe_workspace_bytes", "scmoe_layer_forward",
-           "moe_topk_layer_forward", "moe_top2_layer_forward"]
+           "scmoe_offload_pool_bytes", "scmoe_layer_forward_offload", "moe_topk_layer_forward",
+           "moe_top2_layer_forward"]
 
 
 class Desc(C.Structure):
@@ -78,6 +79,9 @@ def lib():
         _lib.scmoe_workspace_bytes.argtypes = [C.POINTER(Desc), C.POINTER(sz)]
         _lib.scmoe_layer_forward.argtypes = [C.POINTER(Desc), vp, i64, vp, i64, C.POINTER(Weights), vp, i64,
                                              vp, i64, C.POINTER(RoutingOut), vp, sz, vp, vp]
+        _lib.scmoe_offload_pool_bytes.argtypes = [C.POINTER(Desc), i32, C.POINTER(sz)]
+        _lib.scmoe_layer_forward_offload.argtypes = [C.POINTER(Desc), vp, i64, vp, i64, C.POINTER(Weights), vp, i32,
+                                                     i32, vp, vp, i64, vp, sz, vp, vp]
         _lib.moe_topk_layer_forward.argtypes = [C.POINTER(Desc), vp, i64, C.POINTER(Weights), vp, i64,
                                                 C.POINTER(RoutingOut), vp, sz, vp]
         _lib.moe_top2_layer_forward.argtypes = _lib.moe_topk_layer_forward.argtypes
@@ -238,6 +242,24 @@ def scmoe_layer_forward(desc, x_prev, x_cur, weights, y, workspace, residual=Non
         _ld(residual), _ptr(y), _ld(y), None if routing is None else C.byref(routing), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream_main),
         None if stream_aux is None else _stream(stream_aux)), "scmoe_layer_forward")
+
+
+def scmoe_offload_pool_bytes(desc, pool_experts):
+    out = C.c_size_t(0)
+    _check(lib().scmoe_offload_pool_bytes(C.byref(desc), pool_experts, C.byref(out)), "scmoe_offload_pool_bytes")
+    return out.value
+
+
+def scmoe_layer_forward_offload(desc, x_prev, x_cur, weights, expert_pool, pool_experts, host_plan, y, workspace,
+                                async_copy=True, stream_main=None, stream_copy=None):
+    """weights: W1 / W2 / b1 / b2 are host tensors (pinned), everything else on the device;
+    host_plan: pinned int32 host tensor of 2 * E + 1 entries."""
+    assert host_plan.dtype == torch.int32 and not host_plan.is_cuda
+    _check(lib().scmoe_layer_forward_offload(
+        C.byref(desc), _ptr(x_prev), _ld(x_prev), _ptr(x_cur), _ld(x_cur), C.byref(weights), _ptr(expert_pool),
+        pool_experts, 1 if async_copy else 0, _ptr(host_plan), _ptr(y), _ld(y), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream_main),
+        None if stream_copy is None else _stream(stream_copy)), "scmoe_layer_forward_offload")
 
 
 def moe_topk_layer_forward(desc, x, weights, y, workspace, routing=None, stream=None):

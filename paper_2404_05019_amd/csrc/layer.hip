@@ -50,7 +50,7 @@ static int check_desc(const scmoe_desc* D, int kmin, int kmax) {
 // Carves the layer workspace.  Every piece starts on a 256-byte boundary.
 struct LayerWs {
   int32_t* expert_idx; float* gate_w; int32_t* counts; int32_t* offsets; int32_t* dst_row;
-  int32_t* src_token; int32_t* offsets_shared; float* coef; void* disp_ws; size_t disp_bytes;
+  int32_t* src_token; int32_t* offsets_shared; int32_t* offsets_c; float* coef; void* disp_ws; size_t disp_bytes;
   void* x_perm; void* hidden; void* y_perm; void* hidden_s; void* s;
   void* scratch_r; void* scratch_s; size_t scratch_bytes;   // GEMM scratch of the routed / shared chain
   int64_t ldh;   // row stride of hidden and hidden_s
@@ -76,6 +76,7 @@ static LayerWs carve(const scmoe_desc* D, void* base, bool shared) {
   w.dst_row = static_cast<int32_t*>(take(items * 4));
   w.src_token = static_cast<int32_t*>(take(rows * 4));
   w.offsets_shared = static_cast<int32_t*>(take(8));
+  w.offsets_c = static_cast<int32_t*>(take(static_cast<size_t>(D->E + 1) * 4));   // offload: present experts only
   w.coef = static_cast<float*>(take(D->cg_mode ? static_cast<size_t>(D->T) * 8 : 0));
   w.disp_bytes = dispatch_ws_bytes(D->T, D->E, D->k);
   w.disp_ws = take(w.disp_bytes);
@@ -371,6 +372,169 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   SCMOE_TRY(combine(w.y_perm, D->d, D->dtype, w.dst_row, w.gate_w, D->T, D->d, D->k, w.s, D->d, residual, ldres,
                     D->cg_mode != SCMOE_CG_NONE ? w.coef : nullptr, y, ldy, sm));
   return copy_routing(D, w, routing, sm);
+}
+
+// ---- expert offloading with determinate migration (paper Sec. 5.3 and appendix A.3) --------
+
+namespace scmoe {
+// Device pool that receives the migrated experts: slot s holds W1, W2, b1, b2 of one expert.
+struct OffloadPool { unsigned char* W1; unsigned char* W2; float* b1; float* b2; size_t total; };
+static OffloadPool carve_pool(const scmoe_desc* D, void* base, int slots) {
+  OffloadPool p{};
+  size_t off = 0;
+  unsigned char* b = static_cast<unsigned char*>(base);
+  auto take = [&](size_t bytes) {
+    unsigned char* q = b ? b + off : nullptr;
+    off += align256(bytes);
+    return q;
+  };
+  const size_t eb = elem_bytes(D->dtype), n = static_cast<size_t>(slots);
+  p.W1 = take(n * D->F * D->d * eb);
+  p.W2 = take(n * D->d * D->F * eb);
+  p.b1 = reinterpret_cast<float*>(take(n * D->F * 4));
+  p.b2 = reinterpret_cast<float*>(take(n * D->d * 4));
+  p.total = off;
+  return p;
+}
+}  // namespace scmoe
+
+extern "C" int scmoe_offload_pool_bytes(const scmoe_desc* D, int32_t pool_experts, size_t* out) {
+  if (!out) return SCMOE_ERR_NULL;
+  SCMOE_TRY(check_desc(D, 1, 2));
+  if (pool_experts < 1 || pool_experts > D->E) return SCMOE_ERR_SHAPE;
+  *out = carve_pool(D, nullptr, pool_experts).total;
+  return SCMOE_OK;
+}
+
+extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_prev, int64_t ld_prev,
+                                           const void* x_cur, int64_t ld_cur, const scmoe_weights* W,
+                                           void* expert_pool, int32_t pool_experts, int32_t async_copy,
+                                           int32_t* host_plan, void* y, int64_t ldy, void* workspace,
+                                           size_t ws_bytes, void* stream_main, void* stream_copy) {
+  SCMOE_TRY(check_desc(D, 1, 2));
+  SCMOE_TRY(check_weights(D, W, true));
+  if ((W->ld_w1 != 0 && W->ld_w1 != D->d) || (W->ld_w2 != 0 && W->ld_w2 != D->F))
+    return SCMOE_ERR_ARG;                                          // host experts are stored dense
+  if (async_copy != 0 && async_copy != 1) return SCMOE_ERR_ARG;
+  if (pool_experts < 1 || pool_experts > D->E) return SCMOE_ERR_SHAPE;
+  if (D->T == 0) return SCMOE_OK;
+  if (!x_prev || !x_cur || !y || !workspace || !expert_pool || !host_plan) return SCMOE_ERR_NULL;
+  if (!view_ok(x_prev, ld_prev, D->d, D->dtype) || !view_ok(x_cur, ld_cur, D->d, D->dtype) ||
+      !view_ok(y, ldy, D->d, D->dtype) || !aligned16(workspace) ||
+      (reinterpret_cast<uintptr_t>(expert_pool) & 255u) != 0)
+    return SCMOE_ERR_SHAPE;
+  const LayerWs w = carve(D, workspace, true);
+  if (ws_bytes < w.total) return SCMOE_ERR_WORKSPACE;
+  const OffloadPool pool = carve_pool(D, expert_pool, pool_experts);
+  hipStream_t sm = static_cast<hipStream_t>(stream_main);
+  hipStream_t sc = static_cast<hipStream_t>(stream_copy);
+  const bool async = async_copy == 1 && stream_copy != nullptr && sc != sm;
+  const size_t eb = elem_bytes(D->dtype);
+  const int E = D->E;
+
+  // 1. Expert selection on the preceding-layer representation: known this early, so the
+  //    migration below moves exactly the experts that will run (nothing is predicted).
+  SCMOE_TRY(gate_topk(x_prev, ld_prev, D->dtype, W->W_g, W->bias, D->T, D->d, E, D->k, D->normalize,
+                      w.expert_idx, w.gate_w, nullptr, sm));
+  const bool gol = gather_on_load(D);
+  SCMOE_TRY(dispatch(x_prev, ld_prev, D->dtype, w.expert_idx, D->T, D->d, E, D->k, D->capacity, w.counts,
+                     w.offsets, w.dst_row, w.src_token, gol ? nullptr : w.x_perm, D->d, w.disp_ws,
+                     w.disp_bytes, sm));
+  hipError_t he = hipMemcpyAsync(host_plan, w.counts, static_cast<size_t>(E) * 4, hipMemcpyDeviceToHost, sm);
+  if (he != hipSuccess) return hip_fail(he);
+  EventPair* ev = nullptr;
+  if (async) {
+    SCMOE_TRY(get_events(&ev));
+    he = hipEventRecord(ev->fork, sm);          // everything that used the pool before is older than this
+    if (he != hipSuccess) return hip_fail(he);
+  }
+  he = hipStreamSynchronize(sm);                // the host needs the counts to issue the copies
+  if (he != hipSuccess) return hip_fail(he);
+
+  // 2. Plan: present experts take pool slots in expert order, so the packed rows (ordered by
+  //    expert) are the segments of the slots in slot order.
+  int32_t* offs_c = host_plan + E;
+  int m = 0;
+  offs_c[0] = 0;
+  int slot_expert[SCMOE_MAX_EXPERTS];
+  for (int e = 0; e < E; ++e) {
+    if (host_plan[e] > 0) {
+      if (m == pool_experts) return SCMOE_ERR_WORKSPACE;   // more experts selected than the pool holds
+      slot_expert[m] = e;
+      offs_c[m + 1] = offs_c[m] + host_plan[e];
+      ++m;
+    }
+  }
+  hipStream_t cs = async ? sc : sm;
+  if (async) {
+    he = hipStreamWaitEvent(sc, ev->fork, 0);
+    if (he != hipSuccess) return hip_fail(he);
+  }
+  const size_t w_bytes = static_cast<size_t>(D->F) * D->d * eb;
+  for (int s = 0; s < m; ++s) {
+    const size_t e = static_cast<size_t>(slot_expert[s]);
+    he = hipMemcpyAsync(pool.W1 + s * w_bytes, static_cast<const unsigned char*>(W->W1) + e * w_bytes, w_bytes,
+                        hipMemcpyHostToDevice, cs);
+    if (he != hipSuccess) return hip_fail(he);
+    he = hipMemcpyAsync(pool.W2 + s * w_bytes, static_cast<const unsigned char*>(W->W2) + e * w_bytes, w_bytes,
+                        hipMemcpyHostToDevice, cs);
+    if (he != hipSuccess) return hip_fail(he);
+    if (W->b1) {
+      he = hipMemcpyAsync(pool.b1 + static_cast<size_t>(s) * D->F, W->b1 + e * D->F, static_cast<size_t>(D->F) * 4,
+                          hipMemcpyHostToDevice, cs);
+      if (he != hipSuccess) return hip_fail(he);
+    }
+    if (W->b2) {
+      he = hipMemcpyAsync(pool.b2 + static_cast<size_t>(s) * D->d, W->b2 + e * D->d, static_cast<size_t>(D->d) * 4,
+                          hipMemcpyHostToDevice, cs);
+      if (he != hipSuccess) return hip_fail(he);
+    }
+  }
+  he = hipMemcpyAsync(w.offsets_c, offs_c, static_cast<size_t>(m + 1) * 4, hipMemcpyHostToDevice, cs);
+  if (he != hipSuccess) return hip_fail(he);
+  if (async) {
+    he = hipEventRecord(ev->join, sc);
+    if (he != hipSuccess) return hip_fail(he);
+  }
+
+  // 3. Shared expert on the current-layer representation: resident, and it is the computation
+  //    the asynchronous migration hides behind.
+  hipLaunchKernelGGL(set_pair, dim3(1), dim3(64), 0, sm, w.offsets_shared, 0, D->T);
+  SCMOE_TRY(launch_status());
+  FfnArgs se{};
+  se.x = x_cur; se.ldx = ld_cur; se.offsets = w.offsets_shared;
+  se.max_rows = D->T; se.E = 1; se.d = D->d; se.F = D->F;
+  se.W1 = W->W1s; se.ldw1 = D->d; se.b1 = W->b1s;
+  se.W2 = W->W2s; se.ldw2 = D->F; se.b2 = W->b2s;
+  se.hidden = w.hidden_s; se.ldh = w.ldh; se.gelu_mode = D->gelu_mode;
+  se.scratch = w.scratch_bytes ? w.scratch_s : nullptr; se.scratch_bytes = w.scratch_bytes;
+  se.y = w.s; se.ldy = D->d;
+  SCMOE_TRY(expert_ffn_any(se, D->dtype, sm));
+  if (D->cg_mode != SCMOE_CG_NONE)
+    SCMOE_TRY(coef_gate(x_cur, ld_cur, D->dtype, W->W_cg, D->cg_mode, D->T, D->d, w.coef, sm));
+
+  // 4. Routed experts from the pool, then decode and merge.
+  if (async) {
+    he = hipStreamWaitEvent(sm, ev->join, 0);
+    if (he != hipSuccess) return hip_fail(he);
+  }
+  if (m > 0) {
+    FfnArgs a{};
+    a.x = gol ? x_prev : w.x_perm;
+    a.ldx = gol ? ld_prev : D->d;
+    a.gather = gol ? w.src_token : nullptr;
+    a.x_rows = D->T;
+    a.offsets = w.offsets_c;
+    a.max_rows = static_cast<int>(packed_rows(D->T, E, D->k, D->capacity));
+    a.E = m; a.d = D->d; a.F = D->F;
+    a.W1 = pool.W1; a.ldw1 = D->d; a.b1 = W->b1 ? pool.b1 : nullptr;
+    a.W2 = pool.W2; a.ldw2 = D->F; a.b2 = W->b2 ? pool.b2 : nullptr;
+    a.hidden = w.hidden; a.ldh = w.ldh; a.y = w.y_perm; a.ldy = D->d; a.gelu_mode = D->gelu_mode;
+    a.scratch = w.scratch_bytes ? w.scratch_r : nullptr; a.scratch_bytes = w.scratch_bytes;
+    SCMOE_TRY(expert_ffn_any(a, D->dtype, sm));
+  }
+  return combine(w.y_perm, D->d, D->dtype, w.dst_row, w.gate_w, D->T, D->d, D->k, w.s, D->d, nullptr, 0,
+                 D->cg_mode != SCMOE_CG_NONE ? w.coef : nullptr, y, ldy, sm);
 }
 
 extern "C" int moe_topk_layer_forward(const scmoe_desc* D, const void* x, int64_t ldx,

@@ -131,6 +131,20 @@ def test_argument_errors_launch_nothing():
     assert lib.moe_top2_layer_forward(C.byref(desc), P, 64, C.byref(w), P, 64, None, P, need, None) == 6
     assert lib.moe_topk_layer_forward(C.byref(desc), P, 64, C.byref(w), P, 64, None, P, 16, None) == 4
     assert lib.scmoe_set_gemm_variant(5) == 6 and lib.scmoe_set_gemm_variant(0) == 0
+    # expert offloading: pool size, bad pool / plan arguments (all refused before any GPU call)
+    bd = B.make_desc(256, 64, 256, 4, 1, 80, B.BF16)
+    assert B.scmoe_offload_pool_bytes(bd, 4) >= 4 * (2 * 64 * 256 * 2 + (256 + 64) * 4)
+    assert B.scmoe_offload_pool_bytes(bd, 1) % 256 == 0
+    with pytest.raises(B.ScmoeError):
+        B.scmoe_offload_pool_bytes(bd, 5)
+    needb = B.scmoe_workspace_bytes(bd)
+    off = lambda pool, n, asy, plan, w_: lib.scmoe_layer_forward_offload(
+        C.byref(bd), P, 64, P, 64, C.byref(w_), pool, n, asy, plan, P, 64, P, needb, None, None)
+    assert off(None, 4, 1, P, w) == 1 and off(P, 4, 1, None, w) == 1
+    assert off(P, 0, 1, P, w) == 2 and off(P, 5, 1, P, w) == 2
+    assert off(P + 16, 4, 1, P, w) == 2                        # pool alignment
+    assert off(P, 4, 2, P, w) == 6
+    assert off(P, 4, 1, P, B.Weights(P, None, P, None, P, None, P, None, P, None, None, 72, 0)) == 6   # strided host experts
 
 
 def test_zipf_bias_shapes_the_load():

@@ -347,6 +347,66 @@ def test_layer_is_deterministic(oracle):
             assert np.array_equal(r[key], outs[0][1][key])
 
 
+# ------------------------------------------------------------------ expert offloading
+
+def _offload_case(oracle, T, E, k, C_, pool_experts, async_copy, seed):
+    """Routed experts in pinned host memory, migrated on demand: same numbers as the resident
+    layer (combine path), and within the bar of the oracle."""
+    L = inputs.make_layer(T=T, d=128, F=256, E=E, dtype="bf16", seed=seed, biases=True, w_scale=0.05)
+    D = DevLayer(L, "bf16")
+    desc = B.make_desc(T, D.d, D.F, E, k, C_, D.code)
+    ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    # resident reference through the combine path (y in place of a copy of x_cur: no fused decode)
+    y_res = D.x_cur.clone()
+    B.scmoe_layer_forward(desc, D.x_prev, y_res, D.weights, y_res, ws)
+    torch.cuda.synchronize()
+    host = lambda t: None if t is None else t.cpu().pin_memory()
+    hW1, hW2, hb1, hb2 = host(D.W1), host(D.W2), host(D.b1), host(D.b2)
+    wts = B.make_weights(D.Wg, hW1, hW2, D.W1s, D.W2s, D.bias, hb1, hb2, D.b1s, D.b2s, D.Wcg)
+    pool = torch.full((B.scmoe_offload_pool_bytes(desc, pool_experts),), 0x7f, dtype=torch.uint8, device=DEV)
+    plan = torch.zeros(2 * E + 1, dtype=torch.int32).pin_memory()
+    y = torch.empty((T, D.d), dtype=D.tdtype, device=DEV)
+    copy_stream = torch.cuda.Stream()
+    for _ in range(2):                                   # the pool is reused from call to call
+        B.scmoe_layer_forward_offload(desc, D.x_prev, D.x_cur, wts, pool, pool_experts, plan, y, ws,
+                                      async_copy=async_copy, stream_copy=copy_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_res)
+    ref, rr = oracle.layer_forward(L["x_prev"], L["x_cur"], L, k=k, capacity_=C_, shared=1,
+                                   normalize=0)
+    assert relerr(to_host(y), ref) <= TOL["bf16"]
+    assert np.array_equal(plan[:E].numpy(), rr["counts"])
+    return plan[:E].numpy()
+
+
+@pytest.mark.parametrize("async_copy", [True, False])
+def test_offload_matches_resident_layer(oracle, async_copy):
+    _offload_case(oracle, 700, 4, 1, 300, 4, async_copy, seed=71)
+    _offload_case(oracle, 600, 8, 2, 200, 8, async_copy, seed=72)          # ScMoE-2 routing
+
+
+def test_offload_decode_step_migrates_only_selected_experts(oracle):
+    """A decode-like step: 3 tokens select at most 3 of 8 experts, and a pool of 3 is enough."""
+    counts = _offload_case(oracle, 3, 8, 1, 3, 3, True, seed=73)
+    assert (counts > 0).sum() <= 3 and counts.sum() == 3
+
+
+def test_offload_pool_too_small_is_an_error(oracle):
+    L = inputs.make_layer(T=500, d=128, F=256, E=8, dtype="bf16", seed=74, w_scale=0.05)
+    D = DevLayer(L, "bf16")
+    desc = B.make_desc(500, D.d, D.F, 8, 1, 500, D.code)
+    ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    host = lambda t: None if t is None else t.cpu().pin_memory()
+    wts = B.make_weights(D.Wg, host(D.W1), host(D.W2), D.W1s, D.W2s, D.bias, None, None, D.b1s, D.b2s, None)
+    pool = torch.empty(B.scmoe_offload_pool_bytes(desc, 2), dtype=torch.uint8, device=DEV)
+    plan = torch.zeros(17, dtype=torch.int32).pin_memory()
+    y = torch.empty((500, D.d), dtype=D.tdtype, device=DEV)
+    with pytest.raises(B.ScmoeError) as e:                # 500 tokens select more than 2 of 8 experts
+        B.scmoe_layer_forward_offload(desc, D.x_prev, D.x_cur, wts, pool, 2, plan, y, ws)
+    assert e.value.status == 4
+    torch.cuda.synchronize()
+
+
 # --------------------------------------------------- full benchmark sizes, sampled rows
 
 def _full_size(oracle, name, n_sample, k=1, shared=True, normalize=0, pad_weights=False):
