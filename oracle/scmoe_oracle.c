@@ -36,6 +36,7 @@
 
 #define ORACLE_GELU_ERF 0
 #define ORACLE_GELU_TANH 1
+#define ORACLE_MAX_TOPK 8
 
 /* Round a double to the nearest bf16 value (ties to even) and return it as a double.
  * Used only by the optional "mimic" mode, which rounds intermediates where a bf16
@@ -99,9 +100,11 @@ void oracle_gate_logits_f64(const float* x, long ldx, const float* Wg, const flo
 }
 
 /*
- * Eq. (2)-(3): top-k selection and gate weights from given logits, k in {1, 2}.
+ * Eq. (2)-(3): top-k selection and gate weights from given logits, 1 <= k <= min(E,
+ * ORACLE_MAX_TOPK) (the paper's layers use k = 1, 2 and, in the Table 4 baselines, 3).
  * Selection: largest logit, lowest index on ties, a NaN never wins over a number (a row
- * of NaNs selects the lowest indices); second choice the same over the remaining experts.
+ * of NaNs selects the lowest indices); each further choice the same over the experts not
+ * chosen yet, so idx[t] lists the k largest logits in descending order.
  * probs = softmax over all E logits (fp64, max subtracted).
  * normalize == 0: w_j = probs[idx_j].  normalize == 1: softmax over the k selected logits
  * only, which is Eq. (2) taken literally (k = 1 gives 1).
@@ -112,11 +115,13 @@ void oracle_gate_topk(const float* logits, int T, int E, int k, int normalize, i
 #pragma omp parallel for schedule(static)
   for (int t = 0; t < T; ++t) {
     const float* l = logits + (long)t * E;
-    int sel[2] = {-1, -1};
+    int sel[ORACLE_MAX_TOPK];
     for (int j = 0; j < k; ++j) {
       int best = -1;
       for (int e = 0; e < E; ++e) {
-        if (j == 1 && e == sel[0]) continue;
+        int taken = 0;                     /* the j-th choice skips the j earlier ones */
+        for (int i = 0; i < j; ++i) taken |= (sel[i] == e);
+        if (taken) continue;
         if (best < 0) { best = e; continue; }
         /* a candidate replaces the best only if strictly larger, or if the best so far
          * is NaN and the candidate is not */
@@ -147,7 +152,7 @@ void oracle_gate_topk(const float* logits, int T, int E, int k, int normalize, i
 /*
  * Sec. 2.2 "input encode" under a capacity C (capacity factor of Tables 8-9).
  * Walk the items in order (all first choices by ascending token, then all second
- * choices).  An item's slot in its expert is the number of earlier items sent there; it
+ * choices, and so on for each further choice).  An item's slot in its expert is the number of earlier items sent there; it
  * is kept iff slot < C.  Kept items are packed expert by expert, in slot order.
  * idx: [T, k]; counts: [E]; offsets: [E+1]; dst_row: [T, k] (-1 = dropped);
  * src_token: [>= number kept].

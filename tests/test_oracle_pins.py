@@ -153,11 +153,34 @@ def test_gate_top2_weights_closed_form(oracle):
     assert (w1 == 1.0).all()
 
 
+@pytest.mark.parametrize("k", [3, 4, 7])
+def test_gate_topk_general(oracle, k):
+    """Eq. (2)-(3) for k > 2 (the top-3 baseline of Table 4): the selection is the k largest
+    logits in descending order (a stable sort gives the lowest index among equals), the
+    normalised weights are p_j / sum of the selected p, the raw ones the softmax entries."""
+    rng = np.random.default_rng(50 + k)
+    logits = (2.0 * rng.standard_normal((300, 7))).astype(np.float32)
+    logits[::5] = np.round(logits[::5])                       # rows with ties
+    idx, w, probs = oracle.gate_topk(logits, k=k, normalize=1)
+    order = np.argsort(-logits, axis=1, kind="stable")[:, :k]
+    assert np.array_equal(idx, order)
+    p = torch.softmax(torch.from_numpy(logits).double(), dim=1).numpy()
+    ps = np.take_along_axis(p, order, 1)
+    assert np.allclose(w, ps / ps.sum(1, keepdims=True), atol=1e-7)
+    _, w0, _ = oracle.gate_topk(logits, k=k, normalize=0)
+    assert np.allclose(w0, ps, atol=1e-7)
+    if k == 7:                                                # k = E: the plain softmax, sorted
+        assert np.allclose(w, ps, atol=1e-7)
+        assert (np.sort(idx, axis=1) == np.arange(7)).all()
+
+
 def test_gate_nan_never_wins(oracle):
     nan = np.float32("nan")
     logits = np.array([[nan, 1.0, 2.0], [0.5, nan, 0.5], [nan, nan, nan], [nan, -5.0, nan]], np.float32)
     idx, _, _ = oracle.gate_topk(logits, k=2)
     assert idx.tolist() == [[2, 1], [0, 2], [0, 1], [1, 0]]
+    idx, _, _ = oracle.gate_topk(logits, k=3)
+    assert idx.tolist() == [[2, 1, 0], [0, 2, 1], [0, 1, 2], [1, 0, 2]]
 
 
 # ------------------------------------------------------------------ dispatch (Sec. 2.2 encode)
@@ -184,13 +207,14 @@ def _dispatch_bruteforce(idx, E, C):
 
 
 @pytest.mark.parametrize("T,E,k,C", [(1, 1, 1, 1), (70, 4, 1, 10), (70, 4, 1, 0), (70, 4, 1, 70),
-                                     (65, 3, 2, 20), (130, 5, 2, 1000), (64, 1, 1, 17)])
+                                     (65, 3, 2, 20), (130, 5, 2, 1000), (64, 1, 1, 17),
+                                     (65, 5, 3, 20), (40, 6, 4, 9)])
 def test_dispatch_bruteforce(oracle, T, E, k, C):
     rng = np.random.default_rng(T * 31 + E)
     if k == 1:
         idx = rng.integers(0, E, (T, 1)).astype(np.int32)
     else:
-        idx = np.stack([rng.permutation(E)[:2] for _ in range(T)]).astype(np.int32)
+        idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
     counts, offsets, dst_row, src_token = oracle.dispatch(idx, E, C)
     bc, bo, bd = _dispatch_bruteforce(idx, E, C)
     assert np.array_equal(counts, bc) and np.array_equal(offsets, bo) and np.array_equal(dst_row, bd)
@@ -378,7 +402,9 @@ def _tiny(seed, T=48, d=12, F=20, E=4, biases=True, cg_rows=0, w_scale=0.3):
     (1, 1, 1000, 0, 0, False), (1, 1, 9, 0, 0, True), (2, 0, 1000, 1, 0, False),
     (2, 0, 14, 1, 0, False), (2, 0, 14, 0, 0, False), (1, 1, 9, 0, 1, False),
     (1, 1, 1000, 0, 2, True), (1, 0, 9, 0, 0, False), (1, 1, 0, 0, 0, False),
-    (2, 1, 14, 1, 0, False), (2, 1, 1000, 0, 1, True)])
+    (2, 1, 14, 1, 0, False), (2, 1, 1000, 0, 1, True), (3, 0, 1000, 1, 0, False),
+    (3, 0, 20, 1, 0, True), (3, 0, 20, 0, 0, False), (3, 1, 20, 1, 2, False),
+    (4, 0, 30, 1, 0, False)])
 def test_layer_bruteforce(oracle, k, shared, C, normalize, cg, res):
     L = _tiny(11 + k + C % 7, cg_rows=cg)
     E = L["Wg"].shape[1]
@@ -494,6 +520,18 @@ def test_two_experts_top2_is_full_mixture(oracle):
             for e in range(2)]
     ref = p[:, :1] * outs[0] + p[:, 1:] * outs[1]
     assert np.allclose(y, ref.numpy(), rtol=1e-6, atol=1e-7)   # gate weights are stored in fp32
+
+
+def test_three_experts_top3_is_full_mixture(oracle):
+    """E = 3, k = 3, no capacity: every expert runs on every token, weighted by the full
+    softmax (Eq. (1) without sparsity), whatever order the selection lists them in."""
+    L = _tiny(33, T=26, E=3, biases=False)
+    y, r = oracle.layer_forward(None, L["x_cur"], L, k=3, shared=0, normalize=1)
+    x = torch.from_numpy(L["x_cur"]).double()
+    p = torch.softmax(x @ torch.from_numpy(L["Wg"]).double(), dim=1)
+    ref = sum(p[:, e:e + 1] * (torch.nn.functional.gelu(x @ torch.from_numpy(L["W1"][e]).double().T)
+                              @ torch.from_numpy(L["W2"][e]).double().T) for e in range(3))
+    assert np.allclose(y, ref.numpy(), rtol=1e-6, atol=1e-7)
 
 
 def test_coefficient_gates(oracle):
