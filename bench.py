@@ -37,6 +37,9 @@ def parse():
                     help="instead of the throughput bench: latency of one block for a decode-like batch of T "
                          "tokens (widths and experts of --workload) with the routed experts resident, offloaded "
                          "with blocking migration, and offloaded with asynchronous migration")
+    ap.add_argument("--layers", action="store_true",
+                    help="instead of the throughput bench: time the layer family of the paper's Table 4 on "
+                         "--workload (standard top-1/2/3 on x_cur, ScMoE and ScMoE-2), one JSON line")
     ap.add_argument("--no-ffn-workspace", action="store_true",
                     help="time the scmoe_expert_ffn leg without its optional scratch (no split-K of the last round)")
     ap.add_argument("--padded-weights", action="store_true",
@@ -114,6 +117,53 @@ def offload_bench(args):
     }))
 
 
+def layers_bench(args):
+    """The layers that Table 4 of the paper sets side by side, on one GPU (no communication, so
+    the differences are compute only): standard top-k on x_cur and ScMoE / ScMoE-2."""
+    import torch
+    from paper_2404_05019_amd import binding as B
+    from paper_2404_05019_amd import inputs
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import DEV, DevLayer
+    L, cfg = inputs.make_config(args.workload)
+    T, d, F, E = cfg["T"], cfg["d"], cfg["F"], cfg["E"]
+    D = DevLayer(L, cfg["dtype"], pad_weights=args.padded_weights)
+    y = torch.empty((T, d), dtype=D.tdtype, device=DEV)
+    offs = torch.empty(E + 1, dtype=torch.int32, device=DEV)
+    res = {}
+    for name, k, shared in (("standard_top1", 1, False), ("standard_top2", 2, False), ("standard_top3", 3, False),
+                            ("scmoe", 1, True), ("scmoe2", 2, True)):
+        if k > E:
+            continue
+        C_ = inputs.capacity(T, E, k, cfg["cf"])
+        desc = B.make_desc(T, d, F, E, k, C_, D.code, 0, 0 if k == 1 else 1, 0)
+        ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+        n = max(T * k, 1)
+        i32 = lambda m: torch.empty(max(m, 1), dtype=torch.int32, device=DEV)
+        keep = dict(expert_idx=i32(n), gate_w=torch.empty(n, dtype=torch.float32, device=DEV), counts=i32(E),
+                    offsets=offs, dst_row=i32(n), src_token=i32(min(n, E * C_)))   # alive while rout is used
+        rout = B.make_routing_out(**keep)
+        if shared:
+            fn = lambda: B.scmoe_layer_forward(desc, D.x_prev, D.x_cur, D.weights, y, ws, routing=rout)
+        else:
+            fn = lambda: B.moe_topk_layer_forward(desc, D.x_cur, D.weights, y, ws, routing=rout)
+        ms = time_region(torch, fn, args.steps, args.warmup)
+        K = int(offs[E].item())
+        flops = 4.0 * (K + (T if shared else 0)) * d * F
+        res[name] = {"ms": round(ms, 4), "tokens_per_s": round(T / (ms * 1e-3), 1), "capacity": C_, "kept_rows": K,
+                     "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 1)}
+        del ws, keep
+    base = res.get("standard_top2", {}).get("ms")
+    for v in res.values():
+        v["speedup_vs_standard_top2"] = round(base / v["ms"], 3) if base else None
+    print(json.dumps({
+        "metric": "layer forward time of the Table 4 layer family (1 MI355X, no communication)", "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": False,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "T": T, "d_model": d, "d_ffn": F, "E": E, "cf": cfg["cf"]},
+        "layers": res}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -132,6 +182,9 @@ def main():
         B.scmoe_set_gemm_variant(args.gemm_variant)
     if args.offload > 0:
         offload_bench(args)
+        return
+    if args.layers:
+        layers_bench(args)
         return
 
     t_gen = time.time()

@@ -60,6 +60,8 @@ enum { SCMOE_CG_NONE = 0, SCMOE_CG_1 = 1, SCMOE_CG_2 = 2 };
 
 /* Upper limit on the number of experts accepted by the gate and dispatch kernels. */
 #define SCMOE_MAX_EXPERTS 64
+/* Upper limit on k, the routed experts per token (the paper's layers use 1, 2 and 3). */
+#define SCMOE_MAX_TOPK 4
 
 /* Shape and options of one layer.  Plain data, host memory, read during the call only. */
 typedef struct scmoe_desc {
@@ -67,8 +69,9 @@ typedef struct scmoe_desc {
   int32_t d;         /* model width                                                   */
   int32_t F;         /* FFN hidden width                                              */
   int32_t E;         /* routed experts, 1..SCMOE_MAX_EXPERTS                          */
-  int32_t k;         /* routed experts per token, 1 or 2 (ScMoE proper uses 1; 2 with the
-                        shared expert is the ScMoE-2 variant of the appendix)          */
+  int32_t k;         /* routed experts per token, 1..min(E, SCMOE_MAX_TOPK).  ScMoE
+                        proper uses 1; 2 with the shared expert is ScMoE-2; the standard
+                        layers of Table 4 use 2 and 3                                  */
   int32_t capacity;  /* C: rows an expert accepts; >= T*k means unbounded             */
   int32_t dtype;     /* SCMOE_F32 / SCMOE_BF16                                        */
   int32_t gelu_mode; /* SCMOE_GELU_ERF / SCMOE_GELU_TANH                              */
@@ -166,6 +169,21 @@ int scmoe_gate_top2(const void* x, int64_t ldx, int32_t dtype, const float* W_g,
                     const float* bias, int32_t T, int32_t d, int32_t E, int32_t normalize,
                     int32_t* expert_idx, float* gate_w, float* probs, void* stream);
 
+/*
+ * Gate routing for any k in 1..min(E, SCMOE_MAX_TOPK) (Eq. (2)-(4); k = 3 is the standard
+ * top-3 layer that Table 4 compares ScMoE-2 with).  Same logits as above.  expert_idx[t,j]
+ * is the arg max among the experts not listed in expert_idx[t,0..j-1] (lowest index on ties,
+ * a NaN never wins), so a row lists the k largest logits in descending order.
+ * normalize == 1: gate_w[t,:] = softmax over the k selected logits; normalize == 0: their
+ * entries of the full softmax.  expert_idx, gate_w: [T, k] row-major.  k = 1 and k = 2 give
+ * exactly what scmoe_gate_top1 / scmoe_gate_top2 give.  SCMOE_ERR_ARG for k outside
+ * 1..SCMOE_MAX_TOPK, SCMOE_ERR_SHAPE for k > E.
+ */
+int scmoe_gate_topk(const void* x, int64_t ldx, int32_t dtype, const float* W_g,
+                    const float* bias, int32_t T, int32_t d, int32_t E, int32_t k,
+                    int32_t normalize, int32_t* expert_idx, float* gate_w, float* probs,
+                    void* stream);
+
 /* Bytes of workspace scmoe_dispatch needs.  `out` is a host pointer. */
 int scmoe_dispatch_workspace_bytes(int32_t T, int32_t E, int32_t k, size_t* out);
 
@@ -174,7 +192,7 @@ int scmoe_dispatch_workspace_bytes(int32_t T, int32_t E, int32_t k, size_t* out)
  * per-expert segments.
  *
  * Items are the (token t, choice j) pairs, ordered by (j, t): every first choice comes
- * before any second choice.  The slot of an item inside its expert e is the number of
+ * before any second choice, every second before any third, and so on.  The slot of an item inside its expert e is the number of
  * earlier items routed to e; the item is kept iff slot < capacity.
  *
  *   counts[e]        = min(#items routed to e, capacity)
@@ -269,7 +287,7 @@ int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out);
  * routed chain on stream_main, forked and joined with events; with stream_aux == NULL
  * everything runs in order on stream_main.  The result is ready on stream_main.
  * desc->k = 1 is ScMoE; desc->k = 2 routes two experts per token on x_prev (ScMoE-2,
- * appendix "more activated experts").  With desc->cg_mode != 0 the coefficient gate reads
+ * appendix "more activated experts"); larger k up to SCMOE_MAX_TOPK follows the same rule.  With desc->cg_mode != 0 the coefficient gate reads
  * x_cur.
  * residual may be NULL.  routing may be NULL.  No host synchronisation happens inside.
  */
@@ -314,7 +332,8 @@ int scmoe_layer_forward_offload(const scmoe_desc* desc, const void* x_prev, int6
 /*
  * Standard top-k MoE layer on the current-layer representation (Eq. (1)-(4); k = 2 is the
  * baseline the paper compares with, Fig. 2(a)):  y = sum_j gate_w[t,j] E_{idx[t,j]}(x[t]).
- * desc->k in {1, 2}.  Shared-expert members of `w` are ignored.
+ * desc->k in 1..min(E, SCMOE_MAX_TOPK); k = 3 is the standard top-3 layer of Table 4, which
+ * has the compute volume of ScMoE-2.  Shared-expert members of `w` are ignored.
  */
 int moe_topk_layer_forward(const scmoe_desc* desc, const void* x, int64_t ldx,
                            const scmoe_weights* w, void* y, int64_t ldy,

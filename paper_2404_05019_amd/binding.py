@@ -19,7 +19,7 @@ MAX_EXPERTS = 64
 
 EXPORTS = ["scmoe_status_string", "scmoe_last_hip_error", "scmoe_set_gemm_variant", "scmoe_padded_ld", "scmoe_capacity",
            "scmoe_gate_top1",
-           "scmoe_gate_top2", "scmoe_dispatch_workspace_bytes", "scmoe_dispatch", "scmoe_expert_ffn",
+           "scmoe_gate_top2", "scmoe_gate_topk", "scmoe_dispatch_workspace_bytes", "scmoe_dispatch", "scmoe_expert_ffn",
            "scmoe_expert_ffn_workspace_bytes",
            "scmoe_combine", "scmoe_coef_gate", "scmoe_workspace_bytes", "scmoe_layer_forward",
            "scmoe_offload_pool_bytes", "scmoe_layer_forward_offload", "moe_topk_layer_forward",
@@ -68,6 +68,7 @@ def lib():
         _lib.scmoe_padded_ld.argtypes = [i32, i32, C.POINTER(i64)]
         _lib.scmoe_gate_top1.argtypes = [vp, i64, i32, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
         _lib.scmoe_gate_top2.argtypes = _lib.scmoe_gate_top1.argtypes
+        _lib.scmoe_gate_topk.argtypes = [vp, i64, i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         _lib.scmoe_dispatch_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
         _lib.scmoe_dispatch.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i64,
                                         vp, sz, vp]
@@ -160,6 +161,13 @@ def scmoe_gate_top1(x, W_g, bias, expert_idx, gate_w, probs=None, normalize=0, s
 def scmoe_gate_top2(x, W_g, bias, expert_idx, gate_w, probs=None, normalize=1, stream=None):
     _gate(lib().scmoe_gate_top2, "scmoe_gate_top2", x, W_g, bias, W_g.shape[1], normalize, expert_idx,
           gate_w, probs, stream)
+
+
+def scmoe_gate_topk(x, W_g, bias, k, expert_idx, gate_w, probs=None, normalize=1, stream=None):
+    T, d = x.shape
+    _check(lib().scmoe_gate_topk(_ptr(x), _ld(x), dtype_code(x), _ptr(W_g), _ptr(bias), T, d,
+                                 W_g.shape[1], int(k), normalize, _ptr(expert_idx), _ptr(gate_w),
+                                 _ptr(probs), _stream(stream)), "scmoe_gate_topk")
 
 
 def scmoe_dispatch_workspace_bytes(T, E, k):

@@ -97,7 +97,7 @@ int combine(const void* y_perm, int64_t ldyp, int dtype, const int32_t* dst_row,
             int64_t ldres, const float* coef, void* y, int64_t ldy, hipStream_t stream) {
   if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
   if (T < 0 || d <= 0 || (d % 8) != 0) return SCMOE_ERR_SHAPE;
-  if (k != 1 && k != 2) return SCMOE_ERR_ARG;
+  if (k < 1 || k > SCMOE_MAX_TOPK) return SCMOE_ERR_ARG;
   if (T == 0) return SCMOE_OK;
   if (!dst_row || !gate_w || !y) return SCMOE_ERR_NULL;
   if (!view_ok(y, ldy, d, dtype)) return SCMOE_ERR_SHAPE;
@@ -119,10 +119,21 @@ int combine(const void* y_perm, int64_t ldyp, int dtype, const int32_t* dst_row,
 #define SCMOE_COMBINE(BF, KK)                                                                       \
   hipLaunchKernelGGL((combine_kernel<BF, KK>), grid, block, 0, stream, yp, ldyp * eb, dst_row, gate_w, T, \
                      vpr, bs, ldbase * eb, rs, ldres * eb, coef, yo, ldy * eb)
+  static_assert(SCMOE_MAX_TOPK == 4, "one instantiation per k below");
   if (dtype == SCMOE_BF16) {
-    if (k == 1) SCMOE_COMBINE(true, 1); else SCMOE_COMBINE(true, 2);
+    switch (k) {
+      case 1: SCMOE_COMBINE(true, 1); break;
+      case 2: SCMOE_COMBINE(true, 2); break;
+      case 3: SCMOE_COMBINE(true, 3); break;
+      default: SCMOE_COMBINE(true, 4); break;
+    }
   } else {
-    if (k == 1) SCMOE_COMBINE(false, 1); else SCMOE_COMBINE(false, 2);
+    switch (k) {
+      case 1: SCMOE_COMBINE(false, 1); break;
+      case 2: SCMOE_COMBINE(false, 2); break;
+      case 3: SCMOE_COMBINE(false, 3); break;
+      default: SCMOE_COMBINE(false, 4); break;
+    }
   }
 #undef SCMOE_COMBINE
   return launch_status();

@@ -2,7 +2,7 @@
 // into per-expert segments.  On one GPU this replaces "encode + All-to-All dispatch".
 //
 // Items are (token t, choice j) pairs in the order i = j*T + t, so every first choice is
-// ranked before any second choice.  The slot of an item is the number of earlier items of
+// ranked before any second choice, every second before any third, and so on.  The slot of an item is the number of earlier items of
 // the same expert.  Positions come from counting (ballot / popcount / prefix sums), never
 // from the arrival order of atomics, so the permutation is reproducible bit for bit.
 //
@@ -163,7 +163,7 @@ int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, i
              hipStream_t stream) {
   if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
   if (T < 0 || E < 1 || E > SCMOE_MAX_EXPERTS || capacity < 0) return SCMOE_ERR_SHAPE;
-  if (k != 1 && k != 2) return SCMOE_ERR_ARG;
+  if (k < 1 || k > SCMOE_MAX_TOPK) return SCMOE_ERR_ARG;
   if (static_cast<int64_t>(T) * k > 0x7fffffffLL) return SCMOE_ERR_SHAPE;
   if (!counts || !offsets) return SCMOE_ERR_NULL;
   if (T > 0 && (!expert_idx || !dst_row || !src_token)) return SCMOE_ERR_NULL;
@@ -202,7 +202,7 @@ int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, i
 extern "C" int scmoe_dispatch_workspace_bytes(int32_t T, int32_t E, int32_t k, size_t* out) {
   if (!out) return SCMOE_ERR_NULL;
   if (T < 0 || E < 1 || E > SCMOE_MAX_EXPERTS) return SCMOE_ERR_SHAPE;
-  if (k != 1 && k != 2) return SCMOE_ERR_ARG;
+  if (k < 1 || k > SCMOE_MAX_TOPK) return SCMOE_ERR_ARG;
   *out = scmoe::dispatch_ws_bytes(T, E, k);
   return SCMOE_OK;
 }

@@ -1,4 +1,4 @@
-// Gate routing (ScMoE paper Eq. (2)-(4)): logits, top-1 / top-2 selection, gate weights.
+// Gate routing (ScMoE paper Eq. (2)-(4)): logits, top-k selection, gate weights.
 //
 // The logits decide an integer (the arg max), so their arithmetic is fixed by the ABI:
 // fp32, one fused multiply-add per input feature in ascending feature order, then one
@@ -152,18 +152,23 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_kernel(
   if (wave == 0) {
     const int t = t0 + lane;
     const float* l = lg + lane * LGS;
-    int sel0 = 0, sel1 = -1;
-    for (int e = 1; e < E; ++e) {
-      const float v = l[e], b = l[sel0];
-      if (v > b || (b != b && v == v)) sel0 = e;
-    }
-    if (k == 2) {
-      for (int e = 0; e < E; ++e) {
-        if (e == sel0) continue;
-        if (sel1 < 0) { sel1 = e; continue; }
-        const float v = l[e], b = l[sel1];
-        if (v > b || (b != b && v == v)) sel1 = e;
+    // the j-th choice: largest logit among the experts not chosen yet, lowest index among
+    // equals, a NaN only if nothing else is left
+    int sel[SCMOE_MAX_TOPK];
+    unsigned long long taken = 0ull;
+#pragma unroll
+    for (int j = 0; j < SCMOE_MAX_TOPK; ++j) {
+      int best = -1;
+      if (j < k) {
+        for (int e = 0; e < E; ++e) {
+          if ((taken >> e) & 1ull) continue;
+          if (best < 0) { best = e; continue; }
+          const float v = l[e], b = l[best];
+          if (v > b || (b != b && v == v)) best = e;
+        }
+        taken |= 1ull << best;
       }
+      sel[j] = best;
     }
     float m = -INFINITY;
     for (int e = 0; e < E; ++e)
@@ -173,19 +178,23 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_kernel(
     row_max[lane] = m;
     row_sum[lane] = sum;
     if (t < T) {
-      if (k == 1) {
-        expert_idx[t] = sel0;
-        gate_w[t] = normalize ? 1.0f : expf(l[sel0] - m) / sum;
-      } else {
-        expert_idx[2 * t] = sel0;
-        expert_idx[2 * t + 1] = sel1;
-        if (normalize) {
-          const float z1 = expf(l[sel1] - l[sel0]);
-          gate_w[2 * t] = 1.0f / (1.0f + z1);
-          gate_w[2 * t + 1] = z1 / (1.0f + z1);
-        } else {
-          gate_w[2 * t] = expf(l[sel0] - m) / sum;
-          gate_w[2 * t + 1] = expf(l[sel1] - m) / sum;
+      // normalize: softmax over the selected logits only, taken relative to the first
+      // (largest) one, whose term is exactly 1
+      float z[SCMOE_MAX_TOPK];
+      float zsum = 0.0f;
+#pragma unroll
+      for (int j = 0; j < SCMOE_MAX_TOPK; ++j) {
+        z[j] = 0.0f;
+        if (j < k) {
+          z[j] = (j == 0) ? 1.0f : expf(l[sel[j]] - l[sel[0]]);
+          zsum += z[j];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < SCMOE_MAX_TOPK; ++j) {
+        if (j < k) {
+          expert_idx[static_cast<int64_t>(t) * k + j] = sel[j];
+          gate_w[static_cast<int64_t>(t) * k + j] = normalize ? z[j] / zsum : expf(l[sel[j]] - m) / sum;
         }
       }
     }
@@ -219,8 +228,8 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
               hipStream_t stream) {
   if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
   if (T < 0 || d <= 0 || (d % 8) != 0 || E < 1 || E > SCMOE_MAX_EXPERTS) return SCMOE_ERR_SHAPE;
-  if (k != 1 && k != 2) return SCMOE_ERR_ARG;
-  if (k == 2 && E < 2) return SCMOE_ERR_SHAPE;
+  if (k < 1 || k > SCMOE_MAX_TOPK) return SCMOE_ERR_ARG;
+  if (k > E) return SCMOE_ERR_SHAPE;
   if (normalize != 0 && normalize != 1) return SCMOE_ERR_ARG;
   if (T == 0) return SCMOE_OK;
   if (!x || !Wg || !idx || !gw) return SCMOE_ERR_NULL;
@@ -249,5 +258,13 @@ extern "C" int scmoe_gate_top2(const void* x, int64_t ldx, int32_t dtype, const 
                                int32_t normalize, int32_t* expert_idx, float* gate_w,
                                float* probs, void* stream) {
   return scmoe::gate_topk(x, ldx, dtype, W_g, bias, T, d, E, 2, normalize, expert_idx, gate_w, probs,
+                          static_cast<hipStream_t>(stream));
+}
+
+extern "C" int scmoe_gate_topk(const void* x, int64_t ldx, int32_t dtype, const float* W_g,
+                               const float* bias, int32_t T, int32_t d, int32_t E, int32_t k,
+                               int32_t normalize, int32_t* expert_idx, float* gate_w,
+                               float* probs, void* stream) {
+  return scmoe::gate_topk(x, ldx, dtype, W_g, bias, T, d, E, k, normalize, expert_idx, gate_w, probs,
                           static_cast<hipStream_t>(stream));
 }

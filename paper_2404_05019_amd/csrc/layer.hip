@@ -38,9 +38,9 @@ static int check_desc(const scmoe_desc* D, int kmin, int kmax) {
   if (D->T < 0 || D->d <= 0 || D->F <= 0 || (D->d % 8) || (D->F % 8) || D->E < 1 ||
       D->E > SCMOE_MAX_EXPERTS || D->capacity < 0)
     return SCMOE_ERR_SHAPE;
-  if (static_cast<int64_t>(D->T) * 2 > 0x7fffffffLL) return SCMOE_ERR_SHAPE;
+  if (static_cast<int64_t>(D->T) * SCMOE_MAX_TOPK > 0x7fffffffLL) return SCMOE_ERR_SHAPE;
   if (D->k < kmin || D->k > kmax) return SCMOE_ERR_ARG;
-  if (D->k == 2 && D->E < 2) return SCMOE_ERR_SHAPE;
+  if (D->k > D->E) return SCMOE_ERR_SHAPE;
   if (D->gelu_mode != SCMOE_GELU_ERF && D->gelu_mode != SCMOE_GELU_TANH) return SCMOE_ERR_ARG;
   if (D->normalize != 0 && D->normalize != 1) return SCMOE_ERR_ARG;
   if (D->cg_mode < SCMOE_CG_NONE || D->cg_mode > SCMOE_CG_2) return SCMOE_ERR_ARG;
@@ -278,7 +278,7 @@ extern "C" int scmoe_expert_ffn_workspace_bytes(int32_t dtype, int32_t d, int32_
 
 extern "C" int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out) {
   if (!out) return SCMOE_ERR_NULL;
-  SCMOE_TRY(check_desc(desc, 1, 2));
+  SCMOE_TRY(check_desc(desc, 1, SCMOE_MAX_TOPK));
   // sized for the shared-expert form; the standard layer uses a prefix of it
   *out = carve(desc, nullptr, true).total;
   return SCMOE_OK;
@@ -304,7 +304,7 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
                                    const void* residual, int64_t ldres, void* y, int64_t ldy,
                                    const scmoe_routing_out* routing, void* workspace,
                                    size_t ws_bytes, void* stream_main, void* stream_aux) {
-  SCMOE_TRY(check_desc(D, 1, 2));
+  SCMOE_TRY(check_desc(D, 1, SCMOE_MAX_TOPK));
   SCMOE_TRY(check_weights(D, W, true));
   if (D->T == 0) return SCMOE_OK;
   if (!x_prev || !x_cur || !y || !workspace) return SCMOE_ERR_NULL;
@@ -400,7 +400,7 @@ static OffloadPool carve_pool(const scmoe_desc* D, void* base, int slots) {
 
 extern "C" int scmoe_offload_pool_bytes(const scmoe_desc* D, int32_t pool_experts, size_t* out) {
   if (!out) return SCMOE_ERR_NULL;
-  SCMOE_TRY(check_desc(D, 1, 2));
+  SCMOE_TRY(check_desc(D, 1, SCMOE_MAX_TOPK));
   if (pool_experts < 1 || pool_experts > D->E) return SCMOE_ERR_SHAPE;
   *out = carve_pool(D, nullptr, pool_experts).total;
   return SCMOE_OK;
@@ -411,7 +411,7 @@ extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_pr
                                            void* expert_pool, int32_t pool_experts, int32_t async_copy,
                                            int32_t* host_plan, void* y, int64_t ldy, void* workspace,
                                            size_t ws_bytes, void* stream_main, void* stream_copy) {
-  SCMOE_TRY(check_desc(D, 1, 2));
+  SCMOE_TRY(check_desc(D, 1, SCMOE_MAX_TOPK));
   SCMOE_TRY(check_weights(D, W, true));
   if ((W->ld_w1 != 0 && W->ld_w1 != D->d) || (W->ld_w2 != 0 && W->ld_w2 != D->F))
     return SCMOE_ERR_ARG;                                          // host experts are stored dense
@@ -541,7 +541,7 @@ extern "C" int moe_topk_layer_forward(const scmoe_desc* D, const void* x, int64_
                                       const scmoe_weights* W, void* y, int64_t ldy,
                                       const scmoe_routing_out* routing, void* workspace,
                                       size_t ws_bytes, void* stream) {
-  SCMOE_TRY(check_desc(D, 1, 2));
+  SCMOE_TRY(check_desc(D, 1, SCMOE_MAX_TOPK));
   SCMOE_TRY(check_weights(D, W, false));
   if (D->T == 0) return SCMOE_OK;
   if (!x || !y || !workspace) return SCMOE_ERR_NULL;

@@ -70,7 +70,7 @@ def test_workspace_sizes_and_desc_checks():
     assert B.scmoe_dispatch_workspace_bytes(0, 4, 1) == 0
     assert B.scmoe_dispatch_workspace_bytes(1000, 4, 2) >= 2 * 8 * 4 * 4
     bad = [dict(T=-1), dict(d=0), dict(d=12), dict(F=100), dict(E=0), dict(E=65), dict(capacity=-1),
-           dict(dtype=7), dict(k=3), dict(k=0), dict(gelu_mode=5), dict(normalize=2), dict(cg_mode=3)]
+           dict(dtype=7), dict(k=5), dict(k=0), dict(k=3, E=2), dict(gelu_mode=5), dict(normalize=2), dict(cg_mode=3)]
     base = dict(T=256, d=64, F=256, E=4, k=1, capacity=80, dtype=B.F32)
     for b in bad:
         with pytest.raises(B.ScmoeError):
@@ -92,11 +92,15 @@ def test_argument_errors_launch_nothing():
     assert lib.scmoe_gate_top1(P + 4, 64, B.F32, P, None, 10, 64, 4, 0, P, P, None, None) == 2  # alignment
     assert lib.scmoe_gate_top1(P, 64, B.F32, P, None, 10, 64, 65, 0, P, P, None, None) == 2     # E too large
     assert lib.scmoe_gate_top2(P, 64, B.F32, P, None, 10, 64, 1, 0, P, P, None, None) == 2      # k=2, E=1
+    assert lib.scmoe_gate_topk(P, 64, B.F32, P, None, 10, 64, 2, 3, 0, P, P, None, None) == 2   # k=3, E=2
+    assert lib.scmoe_gate_topk(P, 64, B.F32, P, None, 10, 64, 8, 5, 0, P, P, None, None) == 6   # k too large
+    assert lib.scmoe_gate_topk(P, 64, B.F32, P, None, 10, 64, 8, 0, 0, P, P, None, None) == 6
+    assert lib.scmoe_gate_topk(None, 64, B.F32, None, None, 0, 64, 4, 3, 0, None, None, None, None) == 0
     assert lib.scmoe_gate_top1(P, 64, B.F32, P, None, 10, 64, 4, 3, P, P, None, None) == 6      # normalize
     assert lib.scmoe_gate_top1(None, 64, B.F32, None, None, 0, 64, 4, 0, None, None, None, None) == 0  # T = 0
     # dispatch: workspace too small, k out of range, NULL outputs
     assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 1, 100, P, P, P, P, P, 64, P, 8, None) == 4
-    assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 3, 100, P, P, P, P, P, 64, P, 1 << 20, None) == 6
+    assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 5, 100, P, P, P, P, P, 64, P, 1 << 20, None) == 6
     assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 1, 100, None, P, P, P, P, 64, P, 1 << 20, None) == 1
     assert lib.scmoe_dispatch(P, 64, B.F32, P, 1000, 64, 4, 1, -1, P, P, P, P, P, 64, P, 1 << 20, None) == 2
     # expert ffn: (x, ld, dtype, offsets, max_rows, E, d, F, W1, ldw1, b1, W2, ldw2, b2, hidden, ldh, y, ldy, gelu,
@@ -111,7 +115,7 @@ def test_argument_errors_launch_nothing():
     assert ffn(None, 64, B.BF16, None, 0, 2, 64, 128, None, 64, None, None, 128, None, None, 128, None, 64, 0, None, 0, None) == 0
     assert ffn(P, 64, B.BF16, P, 100, 2, 64, 128, P, 64, None, P, 128, None, P, 128, P, 64, 0, P + 8, 1 << 30, None) == 2  # workspace alignment
     # combine / coefficient gate
-    assert lib.scmoe_combine(P, 64, B.F32, P, P, 10, 64, 3, None, 0, None, 0, None, P, 64, None) == 6
+    assert lib.scmoe_combine(P, 64, B.F32, P, P, 10, 64, 5, None, 0, None, 0, None, P, 64, None) == 6
     assert lib.scmoe_combine(P, 64, B.F32, None, P, 10, 64, 1, None, 0, None, 0, None, P, 64, None) == 1
     assert lib.scmoe_combine(P, 64, B.F32, P, P, 10, 64, 1, P, 8, None, 0, None, P, 64, None) == 2
     assert lib.scmoe_coef_gate(P, 64, B.F32, P, 0, 10, 64, P, None) == 6
@@ -126,7 +130,7 @@ def test_argument_errors_launch_nothing():
     assert call(desc, B.Weights(P, None, P, None, P, None, None, None, P, None, None, 0, 0), need) == 1
     assert call(desc, B.Weights(P, None, P, None, P, None, P, None, P, None, None, 60, 0), need) == 2     # ld_w1 < d
     assert call(desc, B.Weights(P, None, P, None, P, None, P, None, P, None, None, 0, 258), need) == 2    # ld_w2 % 4
-    assert call(B.make_desc(256, 64, 256, 4, 3, 80, B.F32), w, need * 4) == 6
+    assert call(B.make_desc(256, 64, 256, 4, 5, 80, B.F32), w, need * 4) == 6
     assert call(B.make_desc(256, 64, 256, 4, 1, 80, B.F32, cg_mode=1), w, need * 2) == 1      # W_cg missing
     assert lib.moe_top2_layer_forward(C.byref(desc), P, 64, C.byref(w), P, 64, None, P, need, None) == 6
     assert lib.moe_topk_layer_forward(C.byref(desc), P, 64, C.byref(w), P, 64, None, P, 16, None) == 4

@@ -27,7 +27,9 @@ def _i32(n, fill=None):
 @pytest.mark.parametrize("T,d,E,dtype,k,use_bias", [
     (256, 64, 4, "f32", 1, False), (1000, 384, 8, "bf16", 1, False), (777, 1024, 16, "bf16", 1, True),
     (130, 72, 3, "f32", 2, True), (513, 264, 64, "bf16", 2, False), (64, 8, 1, "bf16", 1, False),
-    (4099, 2048, 16, "bf16", 2, True), (300, 128, 33, "f32", 1, True), (1, 16, 2, "f32", 2, False)])
+    (4099, 2048, 16, "bf16", 2, True), (300, 128, 33, "f32", 1, True), (1, 16, 2, "f32", 2, False),
+    (1500, 256, 8, "bf16", 3, True), (300, 64, 5, "f32", 4, False), (100, 16, 3, "f32", 3, False),
+    (200, 40, 64, "bf16", 4, True)])
 @pytest.mark.parametrize("normalize", [0, 1])
 def test_gate_parity(oracle, T, d, E, dtype, k, use_bias, normalize):
     rng = np.random.default_rng(T + d + E)
@@ -38,8 +40,15 @@ def test_gate_parity(oracle, T, d, E, dtype, k, use_bias, normalize):
     gx, gW, gb = to_dev(x, dtype), to_dev(Wg, "f32"), to_dev(bias, "f32")
     gi, gw = _i32(T * k), torch.empty(T * k, dtype=torch.float32, device=DEV)
     gp = torch.empty((T, E), dtype=torch.float32, device=DEV)
-    fn = B.scmoe_gate_top1 if k == 1 else B.scmoe_gate_top2
-    fn(gx, gW, gb, gi, gw, gp, normalize=normalize)
+    if k <= 2:
+        fn = B.scmoe_gate_top1 if k == 1 else B.scmoe_gate_top2
+        fn(gx, gW, gb, gi, gw, gp, normalize=normalize)
+        # the general entry point gives the same bits for k = 1 and k = 2
+        gi2, gw2 = _i32(T * k), torch.empty(T * k, dtype=torch.float32, device=DEV)
+        B.scmoe_gate_topk(gx, gW, gb, k, gi2, gw2, None, normalize=normalize)
+        assert torch.equal(gi, gi2) and torch.equal(gw, gw2)
+    else:
+        B.scmoe_gate_topk(gx, gW, gb, k, gi, gw, gp, normalize=normalize)
     torch.cuda.synchronize()
     assert np.array_equal(gi.cpu().numpy().reshape(T, k), idx)
     assert np.abs(gw.cpu().numpy().reshape(T, k).astype(np.float64) - w).max() <= 1e-6
@@ -96,16 +105,19 @@ def _run_dispatch(x, idx, E, k, C_, dtype, copy=True):
 @pytest.mark.parametrize("T,E,k,C_,d,dtype", [
     (1, 1, 1, 1, 8, "f32"), (63, 4, 1, 10, 16, "bf16"), (64, 4, 1, 0, 8, "f32"), (257, 4, 1, 257, 24, "bf16"),
     (5000, 8, 1, 700, 64, "bf16"), (5000, 16, 2, 500, 40, "f32"), (1025, 64, 2, 40, 8, "bf16"),
-    (4096, 7, 2, 100000, 8, "f32"), (300, 1, 1, 17, 8, "bf16")])
+    (4096, 7, 2, 100000, 8, "f32"), (300, 1, 1, 17, 8, "bf16"), (3000, 8, 3, 900, 16, "bf16"),
+    (1000, 6, 4, 500, 8, "f32"), (257, 3, 3, 300, 8, "f32")])
 def test_dispatch_parity(oracle, T, E, k, C_, d, dtype):
     rng = np.random.default_rng(T * 7 + E)
     x = inputs.quantize(rng.standard_normal((T, d)), dtype)
     if k == 1:
         idx = rng.integers(0, E, (T, 1)).astype(np.int32)
-    else:
+    elif k == 2:
         a = rng.integers(0, E, T)
         b = (a + 1 + rng.integers(0, E - 1, T)) % E
         idx = np.stack([a, b], 1).astype(np.int32)
+    else:                                             # k distinct experts per token
+        idx = np.argsort(rng.random((T, E)), axis=1)[:, :k].astype(np.int32)
     counts, offsets, dst_row, src_token = oracle.dispatch(idx, E, C_)
     gc, go, gd, gs, gxp = _run_dispatch(x, idx, E, k, C_, dtype)
     K = int(offsets[E])
@@ -224,7 +236,8 @@ def test_expert_ffn_tile_variants(oracle, variant):
 @pytest.mark.parametrize("T,d,k,dtype,use_base,use_res,use_coef", [
     (300, 64, 1, "f32", True, False, False), (257, 384, 1, "bf16", True, True, True),
     (100, 8, 2, "f32", False, False, False), (1000, 1024, 2, "bf16", True, False, True),
-    (64, 2048, 1, "bf16", False, True, False)])
+    (64, 2048, 1, "bf16", False, True, False), (200, 128, 3, "bf16", True, False, False),
+    (90, 64, 4, "f32", True, True, True)])
 def test_combine_parity(oracle, T, d, k, dtype, use_base, use_res, use_coef):
     rng = np.random.default_rng(T + d)
     K = T * k // 2 + 1
@@ -283,7 +296,8 @@ def test_layer_tiny_config(oracle, two_streams):
 @pytest.mark.parametrize("k,shared,C_,normalize,cg,res,gelu", [
     (1, True, 200, 0, 0, False, 0), (1, True, 100000, 0, 1, True, 0), (1, True, 150, 0, 2, False, 1),
     (2, False, 300, 1, 0, False, 0), (2, False, 100000, 0, 0, False, 0), (1, False, 0, 0, 0, False, 0),
-    (1, True, 0, 1, 0, False, 0)])
+    (1, True, 0, 1, 0, False, 0), (3, False, 450, 1, 0, False, 0), (3, False, 100000, 0, 0, False, 1),
+    (4, False, 600, 1, 0, False, 0), (3, True, 450, 1, 1, False, 0)])
 def test_layer_bf16_mfma_path(oracle, k, shared, C_, normalize, cg, res, gelu):
     """bf16 layer on the MFMA path with gather-on-load: ragged T, binding capacity, drops."""
     L = inputs.make_layer(T=700, d=128, F=256, E=4, dtype="bf16", seed=11 + k, biases=True, cg_rows=cg,
@@ -440,6 +454,15 @@ def test_full_size_medium_and_top2_baseline(oracle):
     assert cfg["C"] == 2560
     cfg2, r2 = _full_size(oracle, "medium", 64, k=2, shared=False, normalize=1)
     assert int(r2["offsets"][-1]) <= 2 * cfg["T"]
+
+
+def test_full_size_medium_top3_and_scmoe2(oracle):
+    """The two layers of equal compute volume that Table 4 sets side by side: the standard
+    top-3 layer and ScMoE-2 (two routed experts on x_prev plus the shared expert)."""
+    cfg3, r3 = _full_size(oracle, "medium", 64, k=3, shared=False, normalize=1)
+    assert int(r3["offsets"][-1]) <= 3 * cfg3["T"]
+    assert (np.sort(r3["idx"], axis=1)[:, 1:] != np.sort(r3["idx"], axis=1)[:, :-1]).all()   # distinct experts
+    _full_size(oracle, "medium", 64, k=2, shared=True, normalize=1)
 
 
 def test_full_size_skewed(oracle):
