@@ -203,6 +203,24 @@ def test_expert_ffn_padded_row_strides(oracle, E, lens, d, F, dtype):
     assert np.array_equal(g, g0)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_expert_ffn_random_segments(oracle, seed):
+    """Seeded sweep of the MFMA grouped GEMM: 1-10 segments of 0-700 rows (empty ones
+    included), widths in multiples of 64, dense or padded strides, with and without the
+    split-K workspace, both GELU forms, both tile variants."""
+    rng = np.random.default_rng(9000 + seed)
+    E = int(rng.integers(1, 11))
+    lens = [int(v) for v in rng.integers(0, 701, E) * (rng.random(E) > 0.2)]
+    d, F = 64 * int(rng.integers(1, 9)), 64 * int(rng.integers(1, 13))
+    B.scmoe_set_gemm_variant(seed % 2)
+    try:
+        _ffn_case(oracle, E, lens, d, F, "bf16", bool(rng.integers(0, 2)), int(rng.integers(0, 2)),
+                  extra_rows=int(rng.integers(0, 9)), pad=bool(rng.integers(0, 2)),
+                  workspace=bool(rng.integers(0, 2)))
+    finally:
+        B.scmoe_set_gemm_variant(0)
+
+
 @pytest.mark.parametrize("variant", [0, 1])
 def test_expert_ffn_split_k_tail(oracle, variant):
     """With a workspace the last, partly filled round of tiles is cut along K (here: 3 tiles
@@ -349,6 +367,31 @@ def test_layer_in_place_output(oracle):
     torch.cuda.synchronize()
     assert relerr(to_host(y2), ref) <= TOL["bf16"]
     assert relerr(to_host(y2), to_host(y)) <= 1e-2
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_layer_random_configurations(oracle, seed):
+    """Seeded sweep over shapes and options: widths on and off the MFMA path (multiples of 64
+    or not), 1 to 12 experts, k up to 4, binding and loose capacities, both dtypes, both layer
+    kinds, every merge mode."""
+    rng = np.random.default_rng(7000 + seed)
+    dtype = "bf16" if seed % 3 else "f32"
+    mfma = dtype == "bf16" and seed % 2 == 0
+    step = 64 if mfma else 8
+    d = step * int(rng.integers(1, 7 if mfma else 20))
+    F = step * int(rng.integers(1, 9 if mfma else 24))
+    T = int(rng.integers(1, 900))
+    E = int(rng.integers(1, 13))
+    k = int(rng.integers(1, min(E, 4) + 1))
+    shared = bool(rng.integers(0, 2))
+    cg = int(rng.integers(0, 3)) if shared else 0
+    C_ = int(rng.choice([0, 1, max(1, T * k // (2 * E)), -(-T * k // E), T * k]))
+    L = inputs.make_layer(T=T, d=d, F=F, E=E, dtype=dtype, seed=7100 + seed, biases=bool(rng.integers(0, 2)),
+                          cg_rows=cg, w_scale=0.05 if dtype == "bf16" else 0.1,
+                          zipf=1.2 if seed % 5 == 0 else None)
+    _layer_case(oracle, L, dtype, E, k, C_, shared, normalize=int(rng.integers(0, 2)), cg_mode=cg,
+                gelu_mode=int(rng.integers(0, 2)), residual=shared and bool(rng.integers(0, 2)),
+                two_streams=shared and bool(rng.integers(0, 2)), pad_weights=bool(rng.integers(0, 2)))
 
 
 def test_layer_is_deterministic(oracle):
