@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--streams", type=int, default=1, choices=[1, 2],
                     help="1: all kernels in order on one stream; 2: shared expert on a second stream")
     ap.add_argument("--gemm-variant", type=int, default=None)
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the layer call in a HIP graph and time its replays (launch-bound small workloads)")
     ap.add_argument("--offload", type=int, default=0, metavar="T",
                     help="instead of the throughput bench: latency of one block for a decode-like batch of T "
                          "tokens (widths and experts of --workload) with the routed experts resident, offloaded "
@@ -200,8 +202,17 @@ def main():
     y = torch.empty((T, d), dtype=D.tdtype, device=DEV)
     aux = torch.cuda.Stream() if args.streams == 2 else None
 
-    def step():
+    def eager_step():
         B.scmoe_layer_forward(desc, D.x_prev, D.x_cur, D.weights, y, ws, stream_aux=aux)
+
+    step = eager_step
+    if args.graph:
+        eager_step()                                   # one-time set-up happens outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager_step()
+        step = graph.replay
 
     # ---- the timed region: exactly `steps` layer forwards between two synchronisations ----
     for _ in range(args.warmup):
@@ -310,6 +321,7 @@ def main():
         "dtype": "bf16" if is_mfma else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "d_model": d, "d_ffn": F, "E": E, "top_k": 1,
                    "capacity": C_, "kept_rows": K, "streams": args.streams,
+                   "launch": "hip graph replay" if args.graph else "eager",
                    "weight_rows": "padded (scmoe_padded_ld)" if args.padded_weights else "dense"},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "ops": ops,
         "layer_tflops": round((4.0 * (K + T) * d * F) / (ms_per_step * 1e-3) / 1e12, 2),

@@ -394,6 +394,41 @@ def test_layer_random_configurations(oracle, seed):
                 two_streams=shared and bool(rng.integers(0, 2)), pad_weights=bool(rng.integers(0, 2)))
 
 
+@pytest.mark.parametrize("two_streams", [False, True])
+def test_layer_in_a_hip_graph(oracle, two_streams):
+    """The layer call makes no host synchronisation, allocates nothing and clears its
+    counters with a kernel, so a caller can capture it in a HIP graph.  The graph is replayed
+    on changing inputs with eager work and synchronisations in between; every replay must give
+    the bits of the eager call on the same inputs."""
+    L = inputs.make_layer(T=700, d=128, F=256, E=4, dtype="bf16", seed=77, biases=True, w_scale=0.05)
+    D = DevLayer(L, "bf16")
+    desc = B.make_desc(D.T, D.d, D.F, D.E, 1, 200, D.code)
+    ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    ws_eager = torch.empty_like(ws)
+    xp, xc = D.x_prev.clone(), D.x_cur.clone()
+    y = torch.empty((D.T, D.d), dtype=D.tdtype, device=DEV)
+    y_eager = torch.empty_like(y)
+    aux = torch.cuda.Stream() if two_streams else None
+    B.scmoe_layer_forward(desc, xp, xc, D.weights, y, ws, stream_aux=aux)     # first call: one-time set-up
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        B.scmoe_layer_forward(desc, xp, xc, D.weights, y, ws, stream_aux=aux)
+    ref, _ = oracle.layer_forward(L["x_prev"], L["x_cur"], L, k=1, capacity_=200, shared=1)
+    for rep in range(4):
+        if rep:
+            xp.copy_(torch.roll(D.x_prev, rep, 0))
+            xc.copy_(torch.roll(D.x_cur, 2 * rep, 0))
+        y.fill_(3.0)
+        g.replay()
+        torch.cuda.synchronize()
+        B.scmoe_layer_forward(desc, xp, xc, D.weights, y_eager, ws_eager, stream_aux=aux)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager), "replay %d differs from the eager call" % rep
+        if rep == 0:
+            assert relerr(to_host(y), ref) <= TOL["bf16"]
+
+
 def test_layer_is_deterministic(oracle):
     L = inputs.make_layer(T=3000, d=128, F=256, E=8, dtype="bf16", seed=41, w_scale=0.05)
     D = DevLayer(L, "bf16")
