@@ -90,6 +90,8 @@ int ffn_generic(const FfnArgs& a, int dtype, hipStream_t stream);
 // bf16 MFMA path.  Returns SCMOE_ERR_ARG when the shape is outside what the MFMA kernels
 // cover (the caller then uses ffn_generic).
 int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream);
+// shared expert `se` (one dense segment) and routed experts `rt` with their first GEMMs in one launch
+int ffn_mfma_bf16_pair(const FfnArgs& se, const FfnArgs& rt, hipStream_t stream);
 
 // Row stride the grouped GEMM likes for an operand of `width` columns: rows at a multiple
 // of 512 bytes get 128 bytes of padding.

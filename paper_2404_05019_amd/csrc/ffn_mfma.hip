@@ -27,6 +27,7 @@
 //    Sec. 2.2 "input encode"), and the second GEMM can scatter, scale and add on store
 //    ("output decode"), which lets the layer skip both permuted copies.
 #include "mfma_common.hpp"
+#include <atomic>
 
 namespace scmoe {
 
@@ -86,8 +87,11 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   const unsigned char* abase = nullptr;     // OFF32: p.A / the expert's W, advanced to the item's first k-tile
   const unsigned char* wbase = nullptr;
   auto set_ptrs = [&](int e, int row0, int row_end, int n0, int kb) {   // kb: first k-tile of the item
-    const unsigned char* We = p.W + static_cast<int64_t>(e) * p.N * p.ldw * 2 + static_cast<int64_t>(kb) * RB;
-    abase = p.A + static_cast<int64_t>(kb) * RB;
+    const bool xs = e == p.E;                 // the dense extra segment: operands of its own
+    const int64_t lda = xs ? p.xlda : p.lda, ldw = xs ? p.xldw : p.ldw;
+    const int32_t* gather = xs ? nullptr : p.gather;
+    const unsigned char* We = (xs ? p.xW : p.W + static_cast<int64_t>(e) * p.N * ldw * 2) + static_cast<int64_t>(kb) * RB;
+    abase = (xs ? p.xA : p.A) + static_cast<int64_t>(kb) * RB;
     wbase = We;
 #pragma unroll
     for (int i = 0; i < CFG::A_PER_WAVE; ++i) {
@@ -95,9 +99,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       const int kc = (lane % CPR) ^ swz<CPR>(row);
       int m = row0 + row;
       if (m > row_end - 1) m = row_end - 1;      // rows past the segment re-read its last row
-      const int64_t src = p.gather ? p.gather[m] : m;
-      if constexpr (OFF32) aoff[i] = static_cast<uint32_t>(src * p.lda * 2 + kc * 16);
-      else aptr[i] = abase + src * p.lda * 2 + kc * 16;
+      const int64_t src = gather ? gather[m] : m;
+      if constexpr (OFF32) aoff[i] = static_cast<uint32_t>(src * lda * 2 + kc * 16);
+      else aptr[i] = abase + src * lda * 2 + kc * 16;
     }
 #pragma unroll
     for (int i = 0; i < CFG::B_PER_WAVE; ++i) {
@@ -105,8 +109,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       const int kc = (lane % CPR) ^ swz<CPR>(row);
       int n = n0 + row;
       if (n > p.N - 1) n = p.N - 1;
-      if constexpr (OFF32) boff[i] = static_cast<uint32_t>(static_cast<int64_t>(n) * p.ldw * 2 + kc * 16);
-      else bptr[i] = We + static_cast<int64_t>(n) * p.ldw * 2 + kc * 16;
+      if constexpr (OFF32) boff[i] = static_cast<uint32_t>(static_cast<int64_t>(n) * ldw * 2 + kc * 16);
+      else bptr[i] = We + static_cast<int64_t>(n) * ldw * 2 + kc * 16;
     }
   };
   auto issue_loads = [&](int kt, int stage) {
@@ -241,8 +245,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     for (int j = 0; j < NJ; ++j) {
       const int n = n0 + wave_n * CFG::TN + j * 16 + 4 * lq;
       f32x4_t b = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (p.bias != nullptr && part <= 0 && n < p.N)
-        b = *reinterpret_cast<const f32x4_t*>(p.bias + static_cast<int64_t>(e) * p.N + n);
+      const float* bias = (e == p.E) ? p.xbias : p.bias + static_cast<int64_t>(e) * p.N;
+      if (((e == p.E) ? p.xbias : p.bias) != nullptr && part <= 0 && n < p.N)
+        b = *reinterpret_cast<const f32x4_t*>(bias + n);
 #pragma unroll
       for (int i = 0; i < MI; ++i) acc[i][j] = b;
     }
@@ -320,6 +325,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     const int itn = it + nslots;
     const bool more = itn < sched.nitems;
     const int crow0 = row0, crow_end = row_end, cn0 = n0, cpart = part, cw = it - sched.full;
+    unsigned char* const cC = (e == p.E) ? p.xC : p.C;        // output of the current tile's segment
+    const int64_t cldc = (e == p.E) ? p.xldc : p.ldc;
     lds_barrier();                    // every wave holds its last fragments: LDS is free
     if (more) {
       setup(itn);
@@ -440,7 +447,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
               o.z = add_bf16x2(o.z, a.z);
               o.w = add_bf16x2(o.w, a.w);
             }
-            *reinterpret_cast<uint4*>(p.C + (orow * p.ldc + n) * 2) = o;
+            *reinterpret_cast<uint4*>(cC + (orow * cldc + n) * 2) = o;
           }
         }
       }
@@ -478,15 +485,18 @@ bool ffn_mfma_supported(int d, int F) { return d > 0 && F > 0 && (d % 64) == 0 &
 
 template <class CFG, bool ACT, bool OFF32>
 static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
-  static bool attr_set = false;
-  if (!attr_set) {
+  // the dynamic-LDS limit is a per-device attribute of the kernel: raise it once per device
+  static std::atomic<bool> attr_set[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+  if (dev < 0 || !attr_set[dev].load(std::memory_order_acquire)) {
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<CFG, ACT, OFF32>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, CFG::LDS_BYTES);
     if (err != hipSuccess) return hip_fail(err);
-    attr_set = true;
+    if (dev >= 0) attr_set[dev].store(true, std::memory_order_release);
   }
   // upper bound on row tiles: sum_e ceil(c_e / BM) <= max_rows / BM + E
-  const int mtb = max_rows / CFG::BM + a.E;
+  const int mtb = max_rows / CFG::BM + a.E + (a.xrows + CFG::BM - 1) / CFG::BM;
   a.nt = (a.N + CFG::BN - 1) / CFG::BN;
   int slots = (mtb * a.nt + 7) / 8;                            // tiles per XCD, upper bound
   const int resident = (num_cus() / 8) * CFG::WG_PER_CU;       // workgroups one XCD holds at once
@@ -506,7 +516,8 @@ static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
 template <class CFG, bool ACT>
 static int launch_gemm(const GemmArgs& a, int max_rows, int64_t a_rows, hipStream_t stream) {
   const int64_t lim = int64_t(1) << 32;
-  const bool off32 = a_rows * a.lda * 2 < lim && static_cast<int64_t>(a.N) * a.ldw * 2 < lim;
+  const bool off32 = a_rows * a.lda * 2 < lim && static_cast<int64_t>(a.N) * a.ldw * 2 < lim &&
+                     static_cast<int64_t>(a.xrows) * a.xlda * 2 < lim && static_cast<int64_t>(a.N) * a.xldw * 2 < lim;
   return off32 ? launch_gemm_impl<CFG, ACT, true>(a, max_rows, stream)
                : launch_gemm_impl<CFG, ACT, false>(a, max_rows, stream);
 }
@@ -525,58 +536,103 @@ __global__ void zero_ints(int* p, int n) {
 
 size_t ffn_mfma_scratch_bytes() { return SPLITK_WS_BYTES; }
 
+// Split-K scratch of a call: arrival counters first (every launch leaves them at zero again),
+// then the partial tiles.  Without scratch the last round of tiles is not split.
+struct SplitK { float* parts = nullptr; int* counters = nullptr; };
+static int prepare_splitk(const FfnArgs& a, SplitK& sk, hipStream_t stream) {
+  if (a.scratch == nullptr || a.scratch_bytes < SPLITK_WS_BYTES) return SCMOE_OK;
+  sk.counters = static_cast<int*>(a.scratch);
+  sk.parts = reinterpret_cast<float*>(static_cast<unsigned char*>(a.scratch) + SPLITK_COUNT_BYTES);
+  hipLaunchKernelGGL(zero_ints, dim3(1), dim3(256), 0, stream, sk.counters, SPLITK_PARTS);
+  return launch_status();
+}
+
+// hidden = act(x . W1^T + b1)
+static GemmArgs first_gemm(const FfnArgs& a, const SplitK& sk) {
+  GemmArgs g{};
+  g.A = static_cast<const unsigned char*>(a.x);
+  g.lda = a.ldx;
+  g.gather = a.gather;
+  g.offsets = a.offsets;
+  g.W = static_cast<const unsigned char*>(a.W1);
+  g.ldw = a.ldw1;
+  g.bias = a.b1;
+  g.C = static_cast<unsigned char*>(a.hidden);
+  g.ldc = a.ldh;
+  g.E = a.E;
+  g.N = a.F;
+  g.Kd = a.d;
+  g.gelu_mode = a.gelu_mode;
+  g.splitk_part = sk.parts;
+  g.splitk_count = sk.counters;
+  return g;
+}
+
+// y = hidden . W2^T + b2, optionally decoded on store
+static GemmArgs second_gemm(const FfnArgs& a, const SplitK& sk) {
+  GemmArgs g{};
+  g.A = static_cast<const unsigned char*>(a.hidden);
+  g.lda = a.ldh;
+  g.gather = nullptr;
+  g.offsets = a.offsets;
+  g.W = static_cast<const unsigned char*>(a.W2);
+  g.ldw = a.ldw2;
+  g.bias = a.b2;
+  g.C = static_cast<unsigned char*>(a.y);
+  g.ldc = a.ldy;
+  g.E = a.E;
+  g.N = a.d;
+  g.Kd = a.F;
+  g.gelu_mode = a.gelu_mode;
+  g.scatter = a.scatter;
+  g.row_scale = a.row_scale;
+  g.addend = static_cast<const unsigned char*>(a.addend);
+  g.ldadd = a.ldadd;
+  g.splitk_part = sk.parts;
+  g.splitk_count = sk.counters;
+  return g;
+}
+
 int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   if (!ffn_mfma_supported(a.d, a.F)) return SCMOE_ERR_ARG;
   if (a.max_rows <= 0) return SCMOE_OK;
-  int* counters = nullptr;
-  float* parts = nullptr;
-  if (a.scratch != nullptr && a.scratch_bytes >= SPLITK_WS_BYTES) {
-    // arrival counters first (every launch leaves them at zero again), then the partial tiles
-    counters = static_cast<int*>(a.scratch);
-    parts = reinterpret_cast<float*>(static_cast<unsigned char*>(a.scratch) + SPLITK_COUNT_BYTES);
-    hipLaunchKernelGGL(zero_ints, dim3(1), dim3(256), 0, stream, counters, SPLITK_PARTS);
-    int st0 = launch_status();
-    if (st0 != SCMOE_OK) return st0;
-  }
-  GemmArgs g1{};
-  g1.A = static_cast<const unsigned char*>(a.x);
-  g1.lda = a.ldx;
-  g1.gather = a.gather;
-  g1.offsets = a.offsets;
-  g1.W = static_cast<const unsigned char*>(a.W1);
-  g1.ldw = a.ldw1;
-  g1.bias = a.b1;
-  g1.C = static_cast<unsigned char*>(a.hidden);
-  g1.ldc = a.ldh;
-  g1.E = a.E;
-  g1.N = a.F;
-  g1.Kd = a.d;
-  g1.gelu_mode = a.gelu_mode;
-  g1.splitk_part = parts;
-  g1.splitk_count = counters;
-  int st = launch_variant<true>(g1, a.max_rows, a.gather ? a.x_rows : a.max_rows, stream);
+  SplitK sk;
+  int st = prepare_splitk(a, sk, stream);
   if (st != SCMOE_OK) return st;
-  GemmArgs g2{};
-  g2.A = static_cast<const unsigned char*>(a.hidden);
-  g2.lda = a.ldh;
-  g2.gather = nullptr;
-  g2.offsets = a.offsets;
-  g2.W = static_cast<const unsigned char*>(a.W2);
-  g2.ldw = a.ldw2;
-  g2.bias = a.b2;
-  g2.C = static_cast<unsigned char*>(a.y);
-  g2.ldc = a.ldy;
-  g2.E = a.E;
-  g2.N = a.d;
-  g2.Kd = a.F;
-  g2.gelu_mode = a.gelu_mode;
-  g2.scatter = a.scatter;
-  g2.row_scale = a.row_scale;
-  g2.addend = static_cast<const unsigned char*>(a.addend);
-  g2.ldadd = a.ldadd;
-  g2.splitk_part = parts;
-  g2.splitk_count = counters;
-  return launch_variant<false>(g2, a.max_rows, a.max_rows, stream);
+  st = launch_variant<true>(first_gemm(a, sk), a.max_rows, a.gather ? a.x_rows : a.max_rows, stream);
+  if (st != SCMOE_OK) return st;
+  return launch_variant<false>(second_gemm(a, sk), a.max_rows, a.max_rows, stream);
+}
+
+// The shared expert (one dense segment of se.max_rows rows, no gather) and the routed experts
+// in three launches instead of four: the first GEMMs of both run as one grouped GEMM with the
+// shared expert as an extra segment; the second GEMMs stay apart and in this order, because
+// the routed one may decode into the rows the shared one writes (rt.addend).
+int ffn_mfma_bf16_pair(const FfnArgs& se, const FfnArgs& rt, hipStream_t stream) {
+  if (!ffn_mfma_supported(rt.d, rt.F) || se.d != rt.d || se.F != rt.F || se.E != 1 || se.gather != nullptr ||
+      se.gelu_mode != rt.gelu_mode)
+    return SCMOE_ERR_ARG;
+  if (se.max_rows <= 0) return ffn_mfma_bf16(rt, stream);
+  if (rt.max_rows <= 0) return ffn_mfma_bf16(se, stream);
+  SplitK sks, skr;
+  int st = prepare_splitk(se, sks, stream);
+  if (st != SCMOE_OK) return st;
+  st = prepare_splitk(rt, skr, stream);
+  if (st != SCMOE_OK) return st;
+  GemmArgs g1 = first_gemm(rt, skr);
+  g1.xrows = se.max_rows;
+  g1.xA = static_cast<const unsigned char*>(se.x);
+  g1.xlda = se.ldx;
+  g1.xW = static_cast<const unsigned char*>(se.W1);
+  g1.xldw = se.ldw1;
+  g1.xbias = se.b1;
+  g1.xC = static_cast<unsigned char*>(se.hidden);
+  g1.xldc = se.ldh;
+  st = launch_variant<true>(g1, rt.max_rows, rt.gather ? rt.x_rows : rt.max_rows, stream);
+  if (st != SCMOE_OK) return st;
+  st = launch_variant<false>(second_gemm(se, sks), se.max_rows, se.max_rows, stream);
+  if (st != SCMOE_OK) return st;
+  return launch_variant<false>(second_gemm(rt, skr), rt.max_rows, rt.max_rows, stream);
 }
 
 }  // namespace scmoe

@@ -165,9 +165,11 @@ static int copy_routing(const scmoe_desc* D, const LayerWs& w, const scmoe_routi
 // With fused_y != nullptr the second GEMM decodes in its epilogue instead (Sec. 2.2 "output
 // decode"): row r goes to fused_y[src_token[r], :] += gate_w * expert output, on top of what
 // the shared expert has written there; `before_ffn` (optional) is waited for first.
+// With shared != nullptr (MFMA path, same stream) the shared expert runs here too: its first
+// GEMM rides in the launch of the routed experts' first GEMM as one more segment.
 static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const scmoe_weights* W,
                         const LayerWs& w, hipStream_t stream, void* fused_y = nullptr, int64_t ld_fused = 0,
-                        hipEvent_t before_ffn = nullptr) {
+                        hipEvent_t before_ffn = nullptr, const FfnArgs* shared = nullptr) {
   SCMOE_TRY(gate_topk(x, ldx, D->dtype, W->W_g, W->bias, D->T, D->d, D->E, D->k, D->normalize,
                       w.expert_idx, w.gate_w, nullptr, stream));
   const bool gol = gather_on_load(D);
@@ -196,6 +198,7 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
     a.y = fused_y; a.ldy = ld_fused;
     a.scatter = w.src_token; a.row_scale = w.gate_w; a.addend = fused_y; a.ldadd = ld_fused;
   }
+  if (shared != nullptr) return ffn_mfma_bf16_pair(*shared, a, stream);
   return expert_ffn_any(a, D->dtype, stream);
 }
 
@@ -352,7 +355,10 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   se.scratch = w.scratch_bytes ? w.scratch_s : nullptr; se.scratch_bytes = w.scratch_bytes;
   se.y = fused ? y : w.s;
   se.ldy = fused ? ldy : D->d;
-  SCMOE_TRY(expert_ffn_any(se, D->dtype, s_shared));
+  // One stream and the MFMA path: the shared expert's first GEMM joins the routed experts'
+  // (one launch over E + 1 segments); otherwise the shared expert runs on its own here.
+  const bool joint = !two && gather_on_load(D);
+  if (!joint) SCMOE_TRY(expert_ffn_any(se, D->dtype, s_shared));
   if (D->cg_mode != SCMOE_CG_NONE)
     SCMOE_TRY(coef_gate(x_cur, ld_cur, D->dtype, W->W_cg, D->cg_mode, D->T, D->d, w.coef, s_shared));
   if (two) {
@@ -361,10 +367,10 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   }
   // routed experts on the preceding-layer representation
   if (fused) {
-    SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, y, ldy, two ? ev->join : nullptr));
+    SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, y, ldy, two ? ev->join : nullptr, joint ? &se : nullptr));
     return copy_routing(D, w, routing, sm);
   }
-  SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm));
+  SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, nullptr, 0, nullptr, joint ? &se : nullptr));
   if (two) {
     hipError_t e = hipStreamWaitEvent(sm, ev->join, 0);
     if (e != hipSuccess) return hip_fail(e);

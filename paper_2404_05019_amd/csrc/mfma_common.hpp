@@ -55,6 +55,18 @@ struct GemmArgs {
   // Split-K of the last, partly filled round of tiles (optional; splitk_part == nullptr: off).
   float* splitk_part;            // SPLITK_PARTS partial tiles of BM x BN floats
   int* splitk_count;             // SPLITK_PARTS arrival counters, zero between launches
+  // Optional dense extra segment with operands of its own (xrows == 0: none): xC[r, :] =
+  // act(xA[r, :] . xW^T + xbias) for r < xrows, same N and Kd.  Its tiles come first in the
+  // tile order and it has the segment id E.  (The shared expert riding in the launch of the
+  // routed experts' first GEMM.)  Not combined with scatter.
+  int xrows;
+  const unsigned char* xA;
+  int64_t xlda;
+  const unsigned char* xW;       // bf16 [N, Kd], row stride xldw
+  int64_t xldw;
+  const float* xbias;            // [N] or nullptr
+  unsigned char* xC;
+  int64_t xldc;
 };
 
 // Scratch of the split-K tail: per XCD as many partial tiles as workgroups are resident
@@ -142,31 +154,38 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 // Persistent tile schedule.  Row tiles are counted from offsets[] on the device (no host
-// round trip).  Workgroup ids congruent mod 8 run on one XCD; XCD x owns the contiguous range
-// [x*chunk, (x+1)*chunk) of the raster order "GM row tiles x all column tiles", and its
-// workgroups take tiles of that range round-robin, so the tiles in flight on one XCD are
-// neighbours and share A and W panels in its L2.
+// round trip).  Workgroup ids congruent mod 8 run on one XCD.  The tiles form up to two
+// ranges, each in the raster order "GM row tiles x all column tiles": the dense extra
+// segment (if any) and the E segments of offsets[].  XCD x owns the x-th eighth of each range
+// (so every XCD gets the same mix of the two kinds of work), and its workgroups take the
+// tiles of its share round-robin, so the tiles in flight on one XCD are neighbours and
+// share A and W panels in its L2.
 template <int BM, int BN, int GM>
 struct TileSchedule {
-  int mt_total, nt, E;
+  int mt_seg, nt, E, xt, xrows;   // row tiles of the offsets[] segments / of the extra segment
   const int32_t* offsets;
   int nslots;
+  int a0, na, b0;                 // this XCD's share: tiles a0 .. a0+na-1 of the extra segment's
+                                  // range, then tiles from b0 on of the other range
   // Work items of this XCD: its `full` tiles that fill whole rounds of nslots workgroups, then
   // the `rem` tiles of the last round, each cut along K into S parts so that the round keeps
-  // (nearly) all workgroups busy.  Item it < full is tile c0 + it; item full + w is part w % S
-  // of tile c0 + full + w / S.  A workgroup takes items slot, slot + nslots, ...
-  int c0, full, rem, S, nitems, xcd;
+  // (nearly) all workgroups busy.  Item it < full is local tile it; item full + w is part
+  // w % S of local tile full + w / S.  A workgroup takes items slot, slot + nslots, ...
+  int full, rem, S, nitems, xcd;
 
   __device__ __forceinline__ TileSchedule(const GemmArgs& p, int nk, bool can_split)
-      : mt_total(0), nt(p.nt), E(p.E), offsets(p.offsets) {
-    for (int q = 0; q < E; ++q) mt_total += (offsets[q + 1] - offsets[q] + BM - 1) / BM;
-    const int total = mt_total * nt;
-    const int chunk = (total + 7) >> 3;
+      : mt_seg(0), nt(p.nt), E(p.E), xt((p.xrows + BM - 1) / BM), xrows(p.xrows), offsets(p.offsets) {
+    for (int q = 0; q < E; ++q) mt_seg += (offsets[q + 1] - offsets[q] + BM - 1) / BM;
     xcd = blockIdx.x & 7;
     nslots = gridDim.x >> 3;
-    c0 = xcd * chunk;
-    int c1 = (xcd + 1) * chunk < total ? (xcd + 1) * chunk : total;
-    const int n = c1 > c0 ? c1 - c0 : 0;
+    auto share = [&](int total, int& first) {
+      const int chunk = (total + 7) >> 3;
+      first = xcd * chunk;
+      const int last = (xcd + 1) * chunk < total ? (xcd + 1) * chunk : total;
+      return last > first ? last - first : 0;
+    };
+    na = share(xt * nt, a0);
+    const int n = na + share(mt_seg * nt, b0);
     full = (n / nslots) * nslots;
     rem = n - full;
     S = 1;
@@ -178,24 +197,37 @@ struct TileSchedule {
     }
     nitems = full + rem * S;
   }
-  // item -> tile index and part (part < 0: the whole tile)
+  // item -> local tile index and part (part < 0: the whole tile)
   __device__ __forceinline__ void item(int it, int& l, int& part) const {
     if (it < full || S == 1) {
-      l = c0 + it;
+      l = it;
       part = -1;
     } else {
       const int w = it - full;
-      l = c0 + full + w / S;
+      l = full + w / S;
       part = w - (w / S) * S;
     }
   }
-  // tile l -> expert e, packed rows [row0, row_end) (row0 + BM may exceed row_end), column n0
-  __device__ __forceinline__ void locate(int l, int& e, int& row0, int& row_end, int& n0) const {
+  // raster order inside a range of mt row tiles: tile l -> row tile, first column
+  __device__ __forceinline__ void raster(int l, int mt, int& m, int& n0) const {
     const int grp = l / (GM * nt);
-    const int rem = l - grp * GM * nt;
-    const int grows = (mt_total - grp * GM < GM) ? mt_total - grp * GM : GM;
-    int mt = grp * GM + rem % grows;
-    n0 = (rem / grows) * BN;
+    const int r = l - grp * GM * nt;
+    const int grows = (mt - grp * GM < GM) ? mt - grp * GM : GM;
+    m = grp * GM + r % grows;
+    n0 = (r / grows) * BN;
+  }
+  // local tile l -> expert e (E: the dense extra segment), packed rows [row0, row_end)
+  // (row0 + BM may exceed row_end), column n0
+  __device__ __forceinline__ void locate(int l, int& e, int& row0, int& row_end, int& n0) const {
+    int mt;
+    if (l < na) {
+      raster(a0 + l, xt, mt, n0);
+      e = E;
+      row0 = mt * BM;
+      row_end = xrows;
+      return;
+    }
+    raster(b0 + l - na, mt_seg, mt, n0);
     row0 = 0;
     row_end = 1;
     for (e = 0; e < E; ++e) {
@@ -209,7 +241,7 @@ struct TileSchedule {
       }
       mt -= ntile;
     }
-    if (e == E) e = E - 1;   // not reachable for l < total
+    if (e == E) e = E - 1;   // not reachable for a tile of this XCD's share
   }
 };
 

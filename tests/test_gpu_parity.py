@@ -430,11 +430,17 @@ def test_layer_in_a_hip_graph(oracle, two_streams):
 
 
 def test_layer_is_deterministic(oracle):
+    """The same call gives the same bits every time.  One- and two-stream mode launch the
+    GEMMs differently (which tiles end up in a split-K tail differs), so across the modes the
+    routing is identical and the output equal up to that rounding."""
     L = inputs.make_layer(T=3000, d=128, F=256, E=8, dtype="bf16", seed=41, w_scale=0.05)
     D = DevLayer(L, "bf16")
-    outs = [run_layer(D, 1, 300, True, two_streams=(i % 2 == 1)) for i in range(3)]
-    for y, r in outs[1:]:
-        assert np.array_equal(y, outs[0][0])
+    outs = [run_layer(D, 1, 300, True, two_streams=(i % 2 == 1)) for i in range(4)]
+    for i, (y, r) in enumerate(outs[1:], 1):
+        if i % 2 == 0:
+            assert np.array_equal(y, outs[0][0])
+        else:
+            assert np.array_equal(y, outs[1][0]) and relerr(y, outs[0][0]) <= 1e-2
         for key in ("idx", "counts", "offsets", "dst_row", "src_token", "w"):
             assert np.array_equal(r[key], outs[0][1][key])
 
@@ -442,8 +448,10 @@ def test_layer_is_deterministic(oracle):
 # ------------------------------------------------------------------ expert offloading
 
 def _offload_case(oracle, T, E, k, C_, pool_experts, async_copy, seed):
-    """Routed experts in pinned host memory, migrated on demand: same numbers as the resident
-    layer (combine path), and within the bar of the oracle."""
+    """Routed experts in pinned host memory, migrated on demand: the same from call to call,
+    the resident layer's numbers up to the rounding of a different tile schedule (which tiles
+    of a GEMM fall into the split-K tail depends on what shares the launch), and within the
+    bar of the oracle."""
     L = inputs.make_layer(T=T, d=128, F=256, E=E, dtype="bf16", seed=seed, biases=True, w_scale=0.05)
     D = DevLayer(L, "bf16")
     desc = B.make_desc(T, D.d, D.F, E, k, C_, D.code)
@@ -459,11 +467,14 @@ def _offload_case(oracle, T, E, k, C_, pool_experts, async_copy, seed):
     plan = torch.zeros(2 * E + 1, dtype=torch.int32).pin_memory()
     y = torch.empty((T, D.d), dtype=D.tdtype, device=DEV)
     copy_stream = torch.cuda.Stream()
+    first = None
     for _ in range(2):                                   # the pool is reused from call to call
         B.scmoe_layer_forward_offload(desc, D.x_prev, D.x_cur, wts, pool, pool_experts, plan, y, ws,
                                       async_copy=async_copy, stream_copy=copy_stream)
         torch.cuda.synchronize()
-        assert torch.equal(y, y_res)
+        assert relerr(to_host(y), to_host(y_res)) <= 1e-2
+        assert first is None or torch.equal(y, first)
+        first = y.clone()
     ref, rr = oracle.layer_forward(L["x_prev"], L["x_cur"], L, k=k, capacity_=C_, shared=1,
                                    normalize=0)
     assert relerr(to_host(y), ref) <= TOL["bf16"]
