@@ -49,6 +49,9 @@ def parse():
                          "instead of dense rows")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured ceilings (a plain device copy and the vendor library's dense bf16 "
+                         "GEMM on the two FFN shapes), which put the roofline fractions beside what is achievable")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     return ap.parse_args()
@@ -260,6 +263,31 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- measured ceilings on this machine: context for the fractions of the published peaks ----
+    ceilings = None
+    if not args.no_ceilings and dtype == "bf16" and rows > 0:
+        n_copy = 1 << 30
+        src = torch.empty(n_copy, dtype=torch.uint8, device=DEV).fill_(1)
+        dst = torch.empty(n_copy, dtype=torch.uint8, device=DEV)
+        ms_copy = time_region(torch, lambda: dst.copy_(src), 10, 3)
+        del src, dst
+        a1 = torch.randn((rows, d), dtype=torch.bfloat16, device=DEV)
+        w1 = torch.randn((F, d), dtype=torch.bfloat16, device=DEV) * 0.02
+        a2 = torch.randn((rows, F), dtype=torch.bfloat16, device=DEV)
+        w2 = torch.randn((d, F), dtype=torch.bfloat16, device=DEV) * 0.02
+        o1 = torch.empty((rows, F), dtype=torch.bfloat16, device=DEV)
+        o2 = torch.empty((rows, d), dtype=torch.bfloat16, device=DEV)
+        ms_v1 = time_region(torch, lambda: torch.matmul(a1, w1.t(), out=o1), 10, 3)
+        ms_v2 = time_region(torch, lambda: torch.matmul(a2, w2.t(), out=o2), 10, 3)
+        del a1, w1, a2, w2, o1, o2
+        gf = 2.0 * rows * d * F
+        ceilings = {
+            "device_copy_GB/s": round(2.0 * n_copy / (ms_copy * 1e-3) / 1e9, 1),
+            "vendor_dense_gemm_TFLOP/s": {"x[%d,%d].W1^T[%d,%d]" % (rows, d, d, F): round(gf / (ms_v1 * 1e-3) / 1e12, 1),
+                                          "h[%d,%d].W2^T[%d,%d]" % (rows, F, F, d): round(gf / (ms_v2 * 1e-3) / 1e12, 1)},
+            "note": "torch.matmul (hipBLASLt), one dense bf16 GEMM of all rows, no bias, no GELU, no routing",
+        }
+
     # algorithmic work per unit (kept row / token) of each operator
     ffn_flops = 4.0 * K * d * F                       # two GEMMs of 2*K*d*F each
     gate_bytes = T * (d * eb + 8)
@@ -323,7 +351,7 @@ def main():
                    "capacity": C_, "kept_rows": K, "streams": args.streams,
                    "launch": "hip graph replay" if args.graph else "eager",
                    "weight_rows": "padded (scmoe_padded_ld)" if args.padded_weights else "dense"},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "ops": ops,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "ops": ops, "ceilings": ceilings,
         "layer_tflops": round((4.0 * (K + T) * d * F) / (ms_per_step * 1e-3) / 1e12, 2),
         "input_generation_s": round(t_gen, 1),
     }
