@@ -102,4 +102,17 @@ inline int64_t padded_ld(int64_t width, int dtype) {
 bool ffn_mfma_supported(int d, int F);
 size_t ffn_mfma_scratch_bytes();   // scratch the MFMA path can use (16-byte aligned)
 
+// Compute units of the current device (256 on MI355X), cached per device.
+inline int num_cus() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 }  // namespace scmoe

@@ -4,8 +4,8 @@
 // fp32, one fused multiply-add per input feature in ascending feature order, then one
 // rounded add of the bias.  The kernel keeps that chain intact per (token, expert) and
 // finds its parallelism elsewhere: a workgroup owns 64 tokens, lane = token, and each of
-// its four waves owns a contiguous group of EPL experts, so every lane runs EPL independent
-// FMA chains.  x is staged through LDS in [64 tokens x 256 bytes] tiles (coalesced HBM
+// its four (or, to fill the chip at smaller T, eight) waves owns a contiguous group of EPL
+// experts, so every lane runs EPL independent FMA chains.  x is staged through LDS in [64 tokens x 256 bytes] tiles (coalesced HBM
 // reads although each lane walks its own row), and so is the matching slab of W_g, which all
 // lanes of a wave then read at one address (an LDS broadcast); the next tile of both is
 // prefetched into registers while the current one is consumed.  Tried without gain: W_g
@@ -17,19 +17,20 @@
 namespace scmoe {
 
 constexpr int GATE_TOK = 64;            // tokens per workgroup (one per lane)
-constexpr int GATE_THREADS = 256;       // four waves
 constexpr int GATE_ROW_BYTES = 256;     // bytes of one token row staged per tile
 constexpr int GATE_ROW_STRIDE = 272;    // LDS row stride: +16 B keeps the row reads conflict-free
-constexpr int GATE_XV = GATE_TOK * 16 / GATE_THREADS;   // 16-byte pieces of x per thread and tile
 
-template <int EPL, bool BF16>
-__global__ __launch_bounds__(GATE_THREADS) void gate_kernel(
+// NW waves per workgroup, each owning EPL experts.
+template <int EPL, int NW, bool BF16>
+__global__ __launch_bounds__(64 * NW) void gate_kernel(
     const unsigned char* __restrict__ x, int64_t ldx, const float* __restrict__ Wg,
     const float* __restrict__ bias, int T, int d, int E, int k, int normalize,
     int32_t* __restrict__ expert_idx, float* __restrict__ gate_w, float* __restrict__ probs) {
   constexpr int EB = BF16 ? 2 : 4;                 // element bytes
   constexpr int KC = GATE_ROW_BYTES / EB;          // features per tile
-  constexpr int EPAD = 4 * EPL;                    // expert columns held in LDS (zero padded)
+  constexpr int GATE_THREADS = 64 * NW;
+  constexpr int GATE_XV = GATE_TOK * 16 / GATE_THREADS;   // 16-byte pieces of x per thread and tile
+  constexpr int EPAD = NW * EPL;                   // expert columns held in LDS (zero padded)
   constexpr int LGS = EPAD + 1;                    // row stride of the logit exchange buffer
   __shared__ __attribute__((aligned(16))) unsigned char xs[GATE_TOK * GATE_ROW_STRIDE];
   constexpr int WS_ELEMS = (KC * EPAD > GATE_TOK * LGS) ? KC * EPAD : GATE_TOK * LGS;
@@ -127,6 +128,9 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_kernel(
               const float4 f = *reinterpret_cast<const float4*>(wrow + q * EPAD + j);
               wv[j] = f.x; wv[j + 1] = f.y; wv[j + 2] = f.z; wv[j + 3] = f.w;
             }
+          } else if (EPL == 2) {
+            const float2 f = *reinterpret_cast<const float2*>(wrow + q * EPAD);
+            wv[0] = f.x; wv[EPL - 1] = f.y;
           } else {
 #pragma unroll
             for (int j = 0; j < EPL; ++j) wv[j] = wrow[q * EPAD + j];
@@ -209,17 +213,17 @@ __global__ __launch_bounds__(GATE_THREADS) void gate_kernel(
   }
 }
 
-template <int EPL>
+template <int EPL, int NW>
 static void launch_gate(int dtype, const void* x, int64_t ldx, const float* Wg, const float* bias,
                         int T, int d, int E, int k, int normalize, int32_t* idx, float* gw,
                         float* probs, hipStream_t stream) {
-  dim3 grid((T + GATE_TOK - 1) / GATE_TOK), block(GATE_THREADS);
+  dim3 grid((T + GATE_TOK - 1) / GATE_TOK), block(64 * NW);
   const unsigned char* xb = static_cast<const unsigned char*>(x);
   if (dtype == SCMOE_BF16)
-    hipLaunchKernelGGL((gate_kernel<EPL, true>), grid, block, 0, stream, xb, ldx, Wg, bias, T, d, E, k,
+    hipLaunchKernelGGL((gate_kernel<EPL, NW, true>), grid, block, 0, stream, xb, ldx, Wg, bias, T, d, E, k,
                        normalize, idx, gw, probs);
   else
-    hipLaunchKernelGGL((gate_kernel<EPL, false>), grid, block, 0, stream, xb, ldx, Wg, bias, T, d, E, k,
+    hipLaunchKernelGGL((gate_kernel<EPL, NW, false>), grid, block, 0, stream, xb, ldx, Wg, bias, T, d, E, k,
                        normalize, idx, gw, probs);
 }
 
@@ -235,11 +239,19 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
   if (!x || !Wg || !idx || !gw) return SCMOE_ERR_NULL;
   if (!view_ok(x, ldx, d, dtype)) return SCMOE_ERR_SHAPE;
   // experts per wave (four waves per workgroup)
-  if (E <= 4) launch_gate<1>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream);
-  else if (E <= 8) launch_gate<2>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream);
-  else if (E <= 16) launch_gate<4>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream);
-  else if (E <= 32) launch_gate<8>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream);
-  else launch_gate<16>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream);
+  // Experts per wave.  Four waves per workgroup do the least redundant work (every wave reads
+  // the whole x tile).  Eight waves with half the experts each pay only where that leaves a
+  // single wave per SIMD with two FMA chains (measured, T = 16384: E = 8 45 -> 34 us, but
+  // E = 16 42 -> 44 us; and E = 16 at T = 32768 94 -> 115 us, E = 8 at T = 8192 17 -> 18 us).
+  const int64_t wgs = (T + GATE_TOK - 1) / GATE_TOK, cus = num_cus();
+  const bool wide = wgs >= cus && wgs < 2 * cus;
+#define SCMOE_GATE(EPL, NW) launch_gate<EPL, NW>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)
+  if (E <= 4) SCMOE_GATE(1, 4);
+  else if (E <= 8) { if (wide) SCMOE_GATE(1, 8); else SCMOE_GATE(2, 4); }
+  else if (E <= 16) SCMOE_GATE(4, 4);
+  else if (E <= 32) SCMOE_GATE(8, 4);
+  else SCMOE_GATE(16, 4);
+#undef SCMOE_GATE
   return launch_status();
 }
 

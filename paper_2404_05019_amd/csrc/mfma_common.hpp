@@ -245,17 +245,4 @@ struct TileSchedule {
   }
 };
 
-// Compute units of the current device (256 on MI355X), cached per device.
-inline int num_cus() {
-  static int cached[64] = {0};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
-    cached[dev] = n;
-  }
-  return cached[dev];
-}
-
 }  // namespace scmoe
