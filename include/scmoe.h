@@ -285,11 +285,17 @@ int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out);
  * The shared expert depends on x_cur only and the routed chain on x_prev only (Sec. 3.2):
  * with stream_aux != NULL the shared expert's GEMMs are enqueued on stream_aux and the
  * routed chain on stream_main, forked and joined with events; with stream_aux == NULL
- * everything runs in order on stream_main.  The result is ready on stream_main.
+ * everything runs in order on stream_main (and, on the bf16 MFMA path, the first GEMMs of the
+ * shared and the routed experts share one launch).  The result is ready on stream_main.
  * desc->k = 1 is ScMoE; desc->k = 2 routes two experts per token on x_prev (ScMoE-2,
- * appendix "more activated experts"); larger k up to SCMOE_MAX_TOPK follows the same rule.  With desc->cg_mode != 0 the coefficient gate reads
- * x_cur.
- * residual may be NULL.  routing may be NULL.  No host synchronisation happens inside.
+ * appendix "more activated experts"); larger k up to SCMOE_MAX_TOPK follows the same rule.
+ * With desc->cg_mode != 0 the coefficient gate reads x_cur.
+ * residual may be NULL.  routing may be NULL.  No host synchronisation happens inside, no
+ * memory is allocated and no memset is enqueued, so the call can be captured in a HIP graph
+ * (after one ordinary call on the device, which creates the events and sets kernel attributes).
+ * Reproducibility: the routing is the same in every mode; y is the same bits for the same
+ * call repeated, but one- and two-stream calls may differ in the last bit (the tiles of a
+ * GEMM that are cut along K depend on what shares its launch).
  */
 int scmoe_layer_forward(const scmoe_desc* desc, const void* x_prev, int64_t ld_prev,
                         const void* x_cur, int64_t ld_cur, const scmoe_weights* w,
@@ -321,7 +327,8 @@ int scmoe_offload_pool_bytes(const scmoe_desc* desc, int32_t pool_experts, size_
  *
  * The call synchronises stream_main once on the host (the host reads the per-expert counts to
  * issue the copies).  SCMOE_ERR_WORKSPACE if more experts are selected than the pool holds.
- * Result: identical, bit for bit, to scmoe_layer_forward's combine path on the same inputs.
+ * Result: the same from call to call; equal to scmoe_layer_forward's on the same inputs up
+ * to rounding (the two launch their GEMMs differently, see there).
  */
 int scmoe_layer_forward_offload(const scmoe_desc* desc, const void* x_prev, int64_t ld_prev,
                                 const void* x_cur, int64_t ld_cur, const scmoe_weights* w,
