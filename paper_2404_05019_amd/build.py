@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libscmoe.so")
-SOURCES = ["gate.hip", "dispatch.hip", "combine.hip", "ffn_generic.hip", "ffn_mfma.hip", "layer.hip"]
+SOURCES = ["gate.hip", "dispatch.hip", "combine.hip", "ffn_generic.hip", "ffn_mfma.hip", "ffn_skinny.hip", "layer.hip"]
 # Packed-fp32 instruction selection is switched off for all device code.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

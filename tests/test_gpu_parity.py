@@ -203,6 +203,32 @@ def test_expert_ffn_padded_row_strides(oracle, E, lens, d, F, dtype):
     assert np.array_equal(g, g0)
 
 
+@pytest.mark.parametrize("E,lens,d,F,biases,gelu_mode,pad", [
+    (4, [3, 0, 7, 1], 128, 256, True, 0, False),
+    (1, [32], 64, 64, False, 0, False),
+    (8, [1] * 8, 192, 448, True, 1, True),
+    (2, [17, 15], 1024, 576, True, 0, False),               # two row subtiles, several k chunks
+    (3, [16, 0, 16], 256, 1088, False, 0, True),
+    (16, [2, 0, 0, 1, 0, 3, 0, 0, 1, 0, 0, 0, 0, 0, 0, 1], 512, 2048, True, 0, False)])
+def test_expert_ffn_few_rows(oracle, E, lens, d, F, biases, gelu_mode, pad):
+    """Calls of at most 32 rows (a decode step) take the weight-streaming kernel."""
+    _ffn_case(oracle, E, lens, d, F, "bf16", biases, gelu_mode, extra_rows=0, pad=pad)
+
+
+@pytest.mark.parametrize("T,E,k,C_,shared,cg,res", [
+    (8, 4, 1, 8, True, 0, False), (20, 8, 1, 3, True, 0, False), (1, 2, 1, 1, True, 0, False),
+    (16, 4, 2, 32, False, 0, False), (10, 8, 3, 30, False, 0, False), (32, 16, 1, 32, True, 1, True),
+    (12, 4, 2, 5, True, 2, False)])
+def test_layer_decode_batches(oracle, T, E, k, C_, shared, cg, res):
+    """Layers of a few tokens (per-token decoding, Sec. 5.3): every GEMM has at most 32 rows."""
+    L = inputs.make_layer(T=T, d=256, F=512, E=E, dtype="bf16", seed=300 + T, biases=True, cg_rows=cg,
+                          w_scale=0.05)
+    _layer_case(oracle, L, "bf16", E, k, C_, shared, normalize=int(k > 1), cg_mode=cg, residual=res)
+    if shared:
+        _layer_case(oracle, L, "bf16", E, k, C_, shared, normalize=int(k > 1), cg_mode=cg, residual=res,
+                    two_streams=True, pad_weights=True)
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_expert_ffn_random_segments(oracle, seed):
     """Seeded sweep of the MFMA grouped GEMM: 1-10 segments of 0-700 rows (empty ones
