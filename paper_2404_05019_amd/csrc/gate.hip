@@ -20,6 +20,59 @@ constexpr int GATE_TOK = 64;            // tokens per workgroup (one per lane)
 constexpr int GATE_ROW_BYTES = 256;     // bytes of one token row staged per tile
 constexpr int GATE_ROW_STRIDE = 272;    // LDS row stride: +16 B keeps the row reads conflict-free
 
+// Top-k selection and gate weights of one token from its E logits `l` (Eq. (2)-(3)); also
+// returns the maximum and the sum of exp(l - max) for the caller's softmax output.
+__device__ __forceinline__ void route_token(const float* l, int E, int k, int normalize, bool write, int64_t t,
+                                            int32_t* __restrict__ expert_idx, float* __restrict__ gate_w,
+                                            float& m_out, float& sum_out) {
+  // the j-th choice: largest logit among the experts not chosen yet, lowest index among
+  // equals, a NaN only if nothing else is left
+  int sel[SCMOE_MAX_TOPK];
+  unsigned long long taken = 0ull;
+#pragma unroll
+  for (int j = 0; j < SCMOE_MAX_TOPK; ++j) {
+    int best = -1;
+    if (j < k) {
+      for (int e = 0; e < E; ++e) {
+        if ((taken >> e) & 1ull) continue;
+        if (best < 0) { best = e; continue; }
+        const float v = l[e], b = l[best];
+        if (v > b || (b != b && v == v)) best = e;
+      }
+      taken |= 1ull << best;
+    }
+    sel[j] = best;
+  }
+  float m = -INFINITY;
+  for (int e = 0; e < E; ++e)
+    if (l[e] > m) m = l[e];
+  float sum = 0.0f;
+  for (int e = 0; e < E; ++e) sum += expf(l[e] - m);
+  m_out = m;
+  sum_out = sum;
+  if (write) {
+    // normalize: softmax over the selected logits only, taken relative to the first
+    // (largest) one, whose term is exactly 1
+    float z[SCMOE_MAX_TOPK];
+    float zsum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < SCMOE_MAX_TOPK; ++j) {
+      z[j] = 0.0f;
+      if (j < k) {
+        z[j] = (j == 0) ? 1.0f : expf(l[sel[j]] - l[sel[0]]);
+        zsum += z[j];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < SCMOE_MAX_TOPK; ++j) {
+      if (j < k) {
+        expert_idx[t * k + j] = sel[j];
+        gate_w[t * k + j] = normalize ? z[j] / zsum : expf(l[sel[j]] - m) / sum;
+      }
+    }
+  }
+}
+
 // NW waves per workgroup, each owning EPL experts.
 template <int EPL, int NW, bool BF16>
 __global__ __launch_bounds__(64 * NW) void gate_kernel(
@@ -153,56 +206,9 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
   }
   __syncthreads();
 
-  if (wave == 0) {
-    const int t = t0 + lane;
-    const float* l = lg + lane * LGS;
-    // the j-th choice: largest logit among the experts not chosen yet, lowest index among
-    // equals, a NaN only if nothing else is left
-    int sel[SCMOE_MAX_TOPK];
-    unsigned long long taken = 0ull;
-#pragma unroll
-    for (int j = 0; j < SCMOE_MAX_TOPK; ++j) {
-      int best = -1;
-      if (j < k) {
-        for (int e = 0; e < E; ++e) {
-          if ((taken >> e) & 1ull) continue;
-          if (best < 0) { best = e; continue; }
-          const float v = l[e], b = l[best];
-          if (v > b || (b != b && v == v)) best = e;
-        }
-        taken |= 1ull << best;
-      }
-      sel[j] = best;
-    }
-    float m = -INFINITY;
-    for (int e = 0; e < E; ++e)
-      if (l[e] > m) m = l[e];
-    float sum = 0.0f;
-    for (int e = 0; e < E; ++e) sum += expf(l[e] - m);
-    row_max[lane] = m;
-    row_sum[lane] = sum;
-    if (t < T) {
-      // normalize: softmax over the selected logits only, taken relative to the first
-      // (largest) one, whose term is exactly 1
-      float z[SCMOE_MAX_TOPK];
-      float zsum = 0.0f;
-#pragma unroll
-      for (int j = 0; j < SCMOE_MAX_TOPK; ++j) {
-        z[j] = 0.0f;
-        if (j < k) {
-          z[j] = (j == 0) ? 1.0f : expf(l[sel[j]] - l[sel[0]]);
-          zsum += z[j];
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < SCMOE_MAX_TOPK; ++j) {
-        if (j < k) {
-          expert_idx[static_cast<int64_t>(t) * k + j] = sel[j];
-          gate_w[static_cast<int64_t>(t) * k + j] = normalize ? z[j] / zsum : expf(l[sel[j]] - m) / sum;
-        }
-      }
-    }
-  }
+  if (wave == 0)
+    route_token(lg + lane * LGS, E, k, normalize, t0 + lane < T, t0 + lane, expert_idx, gate_w, row_max[lane],
+                row_sum[lane]);
   if (probs != nullptr) {
     __syncthreads();
     const int ntok = (T - t0 < GATE_TOK) ? T - t0 : GATE_TOK;
@@ -212,6 +218,103 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
     }
   }
 }
+
+// A few tokens (a decode step): the kernel above would run one workgroup whose lanes each
+// walk a serial chain over 64 tokens' worth of LDS traffic.  Here a lane owns one (token,
+// expert) chain: EPAD = E rounded up to a power of two lanes per token, 256 / EPAD tokens per
+// workgroup.  W_g and the tokens' rows are staged through LDS in chunks of `kch` features
+// with fully coalesced, independent loads (one memory latency per chunk); W_g is transposed
+// on the way in, so a chain reads 4 consecutive features of its expert (and 8 of its token)
+// with one 16-byte LDS read and the reads of many features are in flight at once.  Same
+// chain, same bits.
+// Dynamic LDS: W chunk [E][kch + 4] fp32, then the x chunk [256 / EPAD][kch] with 16 bytes of
+// row padding (both paddings spread the rows over the banks).
+template <bool BF16>
+__global__ __launch_bounds__(256) void gate_small_kernel(
+    const unsigned char* __restrict__ x, int64_t ldx, const float* __restrict__ Wg,
+    const float* __restrict__ bias, int T, int d, int E, int epad, int kch, int k, int normalize,
+    int32_t* __restrict__ expert_idx, float* __restrict__ gate_w, float* __restrict__ probs) {
+  constexpr int EB = BF16 ? 2 : 4;
+  extern __shared__ __attribute__((aligned(16))) unsigned char gsm[];
+  __shared__ float lg[256 + 256];                  // [tokens][epad + 1]
+  __shared__ float row_max[256];
+  __shared__ float row_sum[256];
+  const int tid = threadIdx.x;
+  const int tpw = 256 / epad;                      // tokens per workgroup
+  const int tl = tid / epad, e = tid - tl * epad;
+  const int t = blockIdx.x * tpw + tl;
+  const bool active = t < T && e < E;
+  const int ec = e < E ? e : E - 1;
+  float* wsm = reinterpret_cast<float*>(gsm);
+  const int wrs = kch + 4;                         // float stride of a staged (transposed) W_g row
+  const int xrs = kch * EB + 16;                   // byte stride of a staged x row
+  unsigned char* xsm = gsm + static_cast<size_t>(wrs) * E * 4;
+  float acc = 0.0f;
+  for (int c0 = 0; c0 < d; c0 += kch) {
+    const int kn = (d - c0 < kch) ? d - c0 : kch;  // multiple of 8
+    __syncthreads();                               // the previous chunk has been consumed
+    // rows c0 .. c0 + kn - 1 of W_g are kn * E consecutive floats (a multiple of 8, 32-byte aligned)
+    const float4* wsrc = reinterpret_cast<const float4*>(Wg + static_cast<int64_t>(c0) * E);
+    for (int i = tid; i < kn * E / 4; i += 256) {
+      const float4 w4 = wsrc[i];
+      const float w[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int fl = 4 * i + q, f = fl / E, ee = fl - f * E;   // feature c0 + f, expert ee
+        wsm[ee * wrs + f] = w[q];
+      }
+    }
+    const int vpr = kn * EB / 16;                  // 16-byte pieces per row
+    for (int i = tid; i < tpw * vpr; i += 256) {
+      const int r = i / vpr, v = i - r * vpr;
+      int tr = blockIdx.x * tpw + r;
+      if (tr > T - 1) tr = T - 1;
+      *reinterpret_cast<uint4*>(xsm + r * xrs + v * 16) =
+          *reinterpret_cast<const uint4*>(x + (static_cast<int64_t>(tr) * ldx + c0) * EB + v * 16);
+    }
+    __syncthreads();
+    const unsigned char* xr = xsm + tl * xrs;
+    const float* wc = wsm + ec * wrs;
+#pragma unroll 4
+    for (int i0 = 0; i0 < kn; i0 += 8) {
+      float f[8];
+      if (BF16) {
+        const uint4 v = *reinterpret_cast<const uint4*>(xr + i0 * 2);
+        const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f[2 * q] = __uint_as_float(wd[q] << 16);
+          f[2 * q + 1] = __uint_as_float(wd[q] & 0xffff0000u);
+        }
+      } else {
+        const float4 a = *reinterpret_cast<const float4*>(xr + i0 * 4);
+        const float4 b = *reinterpret_cast<const float4*>(xr + i0 * 4 + 16);
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
+        f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+      }
+      const float4 wlo = *reinterpret_cast<const float4*>(wc + i0);
+      const float4 whi = *reinterpret_cast<const float4*>(wc + i0 + 4);
+      const float wv[8] = {wlo.x, wlo.y, wlo.z, wlo.w, whi.x, whi.y, whi.z, whi.w};
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc = __fmaf_rn(f[q], wv[q], acc);
+    }
+  }
+  if (active) {
+    if (bias != nullptr) acc = __fadd_rn(acc, bias[e]);
+    lg[tl * (epad + 1) + e] = acc;
+  }
+  __syncthreads();
+  if (tid < tpw) {
+    const int tt = blockIdx.x * tpw + tid;
+    if (tt < T) route_token(lg + tid * (epad + 1), E, k, normalize, true, tt, expert_idx, gate_w, row_max[tid], row_sum[tid]);
+  }
+  if (probs != nullptr) {
+    __syncthreads();
+    if (active) probs[static_cast<int64_t>(t) * E + e] = expf(lg[tl * (epad + 1) + e] - row_max[tl]) / row_sum[tl];
+  }
+}
+
+constexpr int GATE_SMALL_LANES = 4096;   // T * EPAD up to which the kernel above is used (16 workgroups)
 
 template <int EPL, int NW>
 static void launch_gate(int dtype, const void* x, int64_t ldx, const float* Wg, const float* bias,
@@ -239,6 +342,29 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
   if (!x || !Wg || !idx || !gw) return SCMOE_ERR_NULL;
   if (!view_ok(x, ldx, d, dtype)) return SCMOE_ERR_SHAPE;
   // experts per wave (four waves per workgroup)
+  int epad = 1;
+  while (epad < E) epad <<= 1;
+  if (static_cast<int64_t>(T) * epad <= GATE_SMALL_LANES && aligned16(Wg)) {   // it copies W_g 16 bytes at a time
+    const int tpw = 256 / epad, eb = elem_bytes(dtype);
+    // features per chunk: W chunk <= 32 KiB, x chunk <= 28 KiB (60 KiB of dynamic LDS beside
+    // the 4 KiB of static arrays), a multiple of 8, no more than d
+    int kch = 8192 / E - 4;
+    const int kx = (28672 / tpw - 16) / eb;
+    if (kx < kch) kch = kx;
+    if (d < kch) kch = d;
+    kch &= ~7;
+    if (kch < 8) kch = 8;
+    const size_t lds = static_cast<size_t>(kch + 4) * E * 4 + static_cast<size_t>(tpw) * (kch * eb + 16);
+    dim3 grid((T + tpw - 1) / tpw), block(256);
+    const unsigned char* xb = static_cast<const unsigned char*>(x);
+    if (dtype == SCMOE_BF16)
+      hipLaunchKernelGGL((gate_small_kernel<true>), grid, block, lds, stream, xb, ldx, Wg, bias, T, d, E, epad, kch,
+                         k, normalize, idx, gw, probs);
+    else
+      hipLaunchKernelGGL((gate_small_kernel<false>), grid, block, lds, stream, xb, ldx, Wg, bias, T, d, E, epad, kch,
+                         k, normalize, idx, gw, probs);
+    return launch_status();
+  }
   // Experts per wave.  Four waves per workgroup do the least redundant work (every wave reads
   // the whole x tile).  Eight waves with half the experts each pay only where that leaves a
   // single wave per SIMD with two FMA chains (measured, T = 16384: E = 8 45 -> 34 us, but
