@@ -4,11 +4,13 @@
 // fp32, one fused multiply-add per input feature in ascending feature order, then one
 // rounded add of the bias.  The kernel keeps that chain intact per (token, expert) and
 // finds its parallelism elsewhere: a workgroup owns 64 tokens, lane = token, and each of
-// its four (or, to fill the chip at smaller T, eight) waves owns a contiguous group of EPL
-// experts, so every lane runs EPL independent FMA chains.  x is staged through LDS in [64 tokens x 256 bytes] tiles (coalesced HBM
-// reads although each lane walks its own row), and so is the matching slab of W_g, which all
-// lanes of a wave then read at one address (an LDS broadcast); the next tile of both is
-// prefetched into registers while the current one is consumed.  Tried without gain: W_g
+// its eight waves (four for E <= 4) owns a contiguous group of EPL experts, so every lane
+// runs EPL independent FMA chains.  x is staged through LDS in [64 tokens x 256 bytes] tiles
+// (coalesced HBM reads although each lane walks its own row), and so is the matching slab
+// of W_g, which all lanes of a wave then read at one address (an LDS broadcast); the next
+// tile of both is prefetched into registers while the current one is consumed (with
+// unconditional loads: predicated ones were each followed by a full wait, and the x pieces
+// then lived in scratch memory).  Tried without gain: W_g
 // through the scalar cache into SGPRs (3x slower: one scalar load per feature and wave) and
 // one W read per 16 features with a DPP row broadcast inside the FMA (same time: LDS traffic
 // is not what bounds the kernel).
@@ -102,21 +104,36 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
   for (int j = 0; j < EPL; ++j) acc[j] = 0.0f;
 
   // this thread's pieces of the x tile: piece c = tid + u*256 -> row c/16, 16-byte column c%16
-  const unsigned char* src[GATE_XV];
-#pragma unroll
-  for (int u = 0; u < GATE_XV; ++u) {
-    const int c = tid + u * GATE_THREADS;
-    int t = t0 + (c >> 4);
+  // The prefetched pieces are four named registers, not an array: as an array written under
+  // `if (more tiles)` they were kept in scratch memory (stored and re-loaded once per tile).
+  static_assert(GATE_XV == 2 || GATE_XV == 4, "pieces of x per thread");
+  auto row_of = [&](int u) {
+    int t = t0 + ((tid + u * GATE_THREADS) >> 4);
     if (t >= T) t = T - 1;
-    src[u] = x + static_cast<int64_t>(t) * ldx * EB + (c & 15) * 16;
-  }
-  uint4 pre[GATE_XV];
+    return x + static_cast<int64_t>(t) * ldx * EB;
+  };
+  const unsigned char* const src0 = row_of(0);
+  const unsigned char* const src1 = row_of(1);
+  const unsigned char* const src2 = row_of(GATE_XV > 2 ? 2 : 0);
+  const unsigned char* const src3 = row_of(GATE_XV > 2 ? 3 : 0);
+  uint4 pre0, pre1, pre2 = {}, pre3 = {};
+  // a piece past the end of a short last tile re-reads piece 0 and is not stored to LDS
+  auto piece = [&](const unsigned char* row, int u, int kc0, int nvec) {
+    const int c15 = (tid + u * GATE_THREADS) & 15;
+    return *reinterpret_cast<const uint4*>(row + static_cast<int64_t>(kc0) * EB + (c15 < nvec ? c15 : 0) * 16);
+  };
   auto fetch = [&](int kc0) {
     const int nvec = ((d - kc0 < KC) ? d - kc0 : KC) * EB / 16;
-#pragma unroll
-    for (int u = 0; u < GATE_XV; ++u)
-      if (((tid + u * GATE_THREADS) & 15) < nvec)
-        pre[u] = *reinterpret_cast<const uint4*>(src[u] + static_cast<int64_t>(kc0) * EB);
+    pre0 = piece(src0, 0, kc0, nvec);
+    pre1 = piece(src1, 1, kc0, nvec);
+    if constexpr (GATE_XV > 2) {
+      pre2 = piece(src2, 2, kc0, nvec);
+      pre3 = piece(src3, 3, kc0, nvec);
+    }
+  };
+  auto stage = [&](int u, const uint4& v, int nvec) {
+    const int c = tid + u * GATE_THREADS;
+    if ((c & 15) < nvec) *reinterpret_cast<uint4*>(xs + (c >> 4) * GATE_ROW_STRIDE + (c & 15) * 16) = v;
   };
   // this thread's pieces of the W_g slab of a tile: KC x EPAD floats, WV float4 pieces each
   constexpr int WV = (KC * EPAD / 4 + GATE_THREADS - 1) / GATE_THREADS;
@@ -143,10 +160,11 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
     const int kn = (d - kc0 < KC) ? d - kc0 : KC;  // features in this tile (multiple of 8)
     const int nvec = kn * EB / 16;                 // 16-byte pieces per row
     __syncthreads();                               // the previous tile has been consumed
-#pragma unroll
-    for (int u = 0; u < GATE_XV; ++u) {
-      const int c = tid + u * GATE_THREADS;
-      if ((c & 15) < nvec) *reinterpret_cast<uint4*>(xs + (c >> 4) * GATE_ROW_STRIDE + (c & 15) * 16) = pre[u];
+    stage(0, pre0, nvec);
+    stage(1, pre1, nvec);
+    if constexpr (GATE_XV > 2) {
+      stage(2, pre2, nvec);
+      stage(3, pre3, nvec);
     }
 #pragma unroll
     for (int u = 0; u < WV; ++u) {
@@ -365,18 +383,15 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
                          k, normalize, idx, gw, probs);
     return launch_status();
   }
-  // Experts per wave.  Four waves per workgroup do the least redundant work (every wave reads
-  // the whole x tile).  Eight waves with half the experts each pay only where that leaves a
-  // single wave per SIMD with two FMA chains (measured, T = 16384: E = 8 45 -> 34 us, but
-  // E = 16 42 -> 44 us; and E = 16 at T = 32768 94 -> 115 us, E = 8 at T = 8192 17 -> 18 us).
-  const int64_t wgs = (T + GATE_TOK - 1) / GATE_TOK, cus = num_cus();
-  const bool wide = wgs >= cus && wgs < 2 * cus;
+  // Eight waves per workgroup, each with an eighth of the experts (measured against four waves
+  // with twice the experts each, bf16: E = 16, T = 32768: 107 -> 89 us; E = 16, T = 16384:
+  // 51 -> 35 us; E = 8, T = 8192: 12.7 -> 8.8 us).
 #define SCMOE_GATE(EPL, NW) launch_gate<EPL, NW>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)
   if (E <= 4) SCMOE_GATE(1, 4);
-  else if (E <= 8) { if (wide) SCMOE_GATE(1, 8); else SCMOE_GATE(2, 4); }
-  else if (E <= 16) SCMOE_GATE(4, 4);
-  else if (E <= 32) SCMOE_GATE(8, 4);
-  else SCMOE_GATE(16, 4);
+  else if (E <= 8) SCMOE_GATE(1, 8);
+  else if (E <= 16) SCMOE_GATE(2, 8);
+  else if (E <= 32) SCMOE_GATE(4, 8);
+  else SCMOE_GATE(8, 8);
 #undef SCMOE_GATE
   return launch_status();
 }
