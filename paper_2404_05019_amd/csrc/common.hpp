@@ -64,6 +64,17 @@ __device__ __forceinline__ float gelu_f32(float v, int mode) {
   return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f));
 }
 
+// Small chores that a layer call would otherwise launch kernels of their own for; the single
+// workgroup of the dispatch scan does them on the side: pair[0..1] = {0, pair_hi} (the segment
+// bounds of the shared expert) and nzero zeros at each of zero_a, zero_b.  All optional.
+struct ScanChores {
+  int32_t* pair = nullptr;
+  int pair_hi = 0;
+  int* zero_a = nullptr;
+  int* zero_b = nullptr;
+  int nzero = 0;
+};
+
 // ---- entry points implemented in one source and used by the layer orchestration --------
 // One expert-FFN call over packed segments.  All strides in elements.
 struct FfnArgs {
@@ -83,6 +94,7 @@ struct FfnArgs {
   const int32_t* scatter; const float* row_scale; const void* addend; int64_t ldadd;
   // Scratch of the MFMA path (split-K of the last round of tiles); may be nullptr: no split.
   void* scratch; size_t scratch_bytes;
+  bool scratch_zeroed;             // the arrival counters at the start of scratch are zero already
 };
 
 int ffn_generic(const FfnArgs& a, int dtype, hipStream_t stream);
@@ -101,6 +113,7 @@ inline int64_t padded_ld(int64_t width, int dtype) {
 }
 bool ffn_mfma_supported(int d, int F);
 size_t ffn_mfma_scratch_bytes();   // scratch the MFMA path can use (16-byte aligned)
+int ffn_mfma_counter_ints();       // ints at the start of that scratch that must be zero before a call
 
 // Compute units of the current device (256 on MI355X), cached per device.
 inline int num_cus() {

@@ -47,8 +47,16 @@ __global__ __launch_bounds__(256) void dispatch_scan(const int32_t* __restrict__
                                                      int E, int capacity,
                                                      int32_t* __restrict__ blockbase,
                                                      int32_t* __restrict__ counts,
-                                                     int32_t* __restrict__ offsets) {
+                                                     int32_t* __restrict__ offsets, const ScanChores ch) {
   __shared__ int cnt[SCMOE_MAX_EXPERTS];
+  if (ch.pair != nullptr && threadIdx.x == 0) {
+    ch.pair[0] = 0;
+    ch.pair[1] = ch.pair_hi;
+  }
+  for (int i = threadIdx.x; i < ch.nzero; i += blockDim.x) {
+    if (ch.zero_a != nullptr) ch.zero_a[i] = 0;
+    if (ch.zero_b != nullptr) ch.zero_b[i] = 0;
+  }
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   for (int e = wave; e < E; e += 4) {
@@ -160,7 +168,7 @@ size_t dispatch_ws_bytes(int T, int E, int k) {
 int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, int T, int d, int E,
              int k, int capacity, int32_t* counts, int32_t* offsets, int32_t* dst_row,
              int32_t* src_token, void* x_perm, int64_t ld_perm, void* workspace, size_t ws_bytes,
-             hipStream_t stream) {
+             hipStream_t stream, const ScanChores* chores) {
   if (!dtype_ok(dtype)) return SCMOE_ERR_DTYPE;
   if (T < 0 || E < 1 || E > SCMOE_MAX_EXPERTS || capacity < 0) return SCMOE_ERR_SHAPE;
   if (k < 1 || k > SCMOE_MAX_TOPK) return SCMOE_ERR_ARG;
@@ -180,7 +188,7 @@ int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, i
   if (nblk > 0)
     hipLaunchKernelGGL(dispatch_hist, dim3(nblk), dim3(DISP_BLOCK), 0, stream, expert_idx, T, k, E, blockhist);
   hipLaunchKernelGGL(dispatch_scan, dim3(1), dim3(256), 0, stream, blockhist, nblk, E, capacity, blockbase,
-                     counts, offsets);
+                     counts, offsets, chores ? *chores : ScanChores{});
   if (nblk > 0) {
     hipLaunchKernelGGL(dispatch_rank, dim3(nblk), dim3(DISP_BLOCK), 0, stream, expert_idx, T, k, E, capacity,
                        blockbase, offsets, dst_row, src_token);
@@ -213,5 +221,5 @@ extern "C" int scmoe_dispatch(const void* x, int64_t ldx, int32_t dtype, const i
                               int32_t* src_token, void* x_perm, int64_t ld_perm, void* workspace,
                               size_t ws_bytes, void* stream) {
   return scmoe::dispatch(x, ldx, dtype, expert_idx, T, d, E, k, capacity, counts, offsets, dst_row,
-                         src_token, x_perm, ld_perm, workspace, ws_bytes, static_cast<hipStream_t>(stream));
+                         src_token, x_perm, ld_perm, workspace, ws_bytes, static_cast<hipStream_t>(stream), nullptr);
 }

@@ -535,6 +535,7 @@ __global__ void zero_ints(int* p, int n) {
 }
 
 size_t ffn_mfma_scratch_bytes() { return SPLITK_WS_BYTES; }
+int ffn_mfma_counter_ints() { return SPLITK_PARTS; }
 
 // Split-K scratch of a call: arrival counters first (every launch leaves them at zero again),
 // then the partial tiles.  Without scratch the last round of tiles is not split.
@@ -543,6 +544,7 @@ static int prepare_splitk(const FfnArgs& a, SplitK& sk, hipStream_t stream) {
   if (a.scratch == nullptr || a.scratch_bytes < SPLITK_WS_BYTES) return SCMOE_OK;
   sk.counters = static_cast<int*>(a.scratch);
   sk.parts = reinterpret_cast<float*>(static_cast<unsigned char*>(a.scratch) + SPLITK_COUNT_BYTES);
+  if (a.scratch_zeroed) return SCMOE_OK;
   hipLaunchKernelGGL(zero_ints, dim3(1), dim3(256), 0, stream, sk.counters, SPLITK_PARTS);
   return launch_status();
 }

@@ -16,7 +16,7 @@ size_t dispatch_ws_bytes(int T, int E, int k);
 int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, int T, int d, int E,
              int k, int capacity, int32_t* counts, int32_t* offsets, int32_t* dst_row,
              int32_t* src_token, void* x_perm, int64_t ld_perm, void* workspace, size_t ws_bytes,
-             hipStream_t stream);
+             hipStream_t stream, const ScanChores* chores);
 int combine(const void* y_perm, int64_t ldyp, int dtype, const int32_t* dst_row, const float* gate_w,
             int T, int d, int k, const void* base, int64_t ldbase, const void* residual,
             int64_t ldres, const float* coef, void* y, int64_t ldy, hipStream_t stream);
@@ -169,13 +169,14 @@ static int copy_routing(const scmoe_desc* D, const LayerWs& w, const scmoe_routi
 // GEMM rides in the launch of the routed experts' first GEMM as one more segment.
 static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const scmoe_weights* W,
                         const LayerWs& w, hipStream_t stream, void* fused_y = nullptr, int64_t ld_fused = 0,
-                        hipEvent_t before_ffn = nullptr, const FfnArgs* shared = nullptr) {
+                        hipEvent_t before_ffn = nullptr, const FfnArgs* shared = nullptr,
+                        const ScanChores* chores = nullptr) {
   SCMOE_TRY(gate_topk(x, ldx, D->dtype, W->W_g, W->bias, D->T, D->d, D->E, D->k, D->normalize,
                       w.expert_idx, w.gate_w, nullptr, stream));
   const bool gol = gather_on_load(D);
   SCMOE_TRY(dispatch(x, ldx, D->dtype, w.expert_idx, D->T, D->d, D->E, D->k, D->capacity, w.counts,
                      w.offsets, w.dst_row, w.src_token, gol ? nullptr : w.x_perm, D->d, w.disp_ws,
-                     w.disp_bytes, stream));
+                     w.disp_bytes, stream, chores));
   const int rows = static_cast<int>(packed_rows(D->T, D->E, D->k, D->capacity));
   FfnArgs a{};
   a.x = gol ? x : w.x_perm;
@@ -190,6 +191,7 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
   a.y = w.y_perm; a.ldy = D->d;
   a.gelu_mode = D->gelu_mode;
   a.scratch = w.scratch_bytes ? w.scratch_r : nullptr; a.scratch_bytes = w.scratch_bytes;
+  a.scratch_zeroed = chores != nullptr && chores->nzero > 0 && chores->zero_a == a.scratch && a.scratch != nullptr;
   if (fused_y) {
     if (before_ffn) {
       hipError_t e = hipStreamWaitEvent(stream, before_ffn, 0);
@@ -198,7 +200,11 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
     a.y = fused_y; a.ldy = ld_fused;
     a.scatter = w.src_token; a.row_scale = w.gate_w; a.addend = fused_y; a.ldadd = ld_fused;
   }
-  if (shared != nullptr) return ffn_mfma_bf16_pair(*shared, a, stream);
+  if (shared != nullptr) {
+    FfnArgs se = *shared;
+    se.scratch_zeroed = chores != nullptr && chores->nzero > 0 && chores->zero_b == se.scratch && se.scratch != nullptr;
+    return ffn_mfma_bf16_pair(se, a, stream);
+  }
   return expert_ffn_any(a, D->dtype, stream);
 }
 
@@ -329,9 +335,23 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
     e = hipStreamWaitEvent(sa, ev->fork, 0);
     if (e != hipSuccess) return hip_fail(e);
   }
-  // shared expert on the current-layer representation (Eq. (6)/(7)): independent of routing
-  hipLaunchKernelGGL(set_pair, dim3(1), dim3(64), 0, s_shared, w.offsets_shared, 0, D->T);
-  SCMOE_TRY(launch_status());
+  // One stream and the MFMA path: the shared expert's first GEMM joins the routed experts'
+  // (one launch over E + 1 segments), and the dispatch scan also writes the shared expert's
+  // segment bounds and clears the split-K counters of both chains; otherwise the shared expert
+  // runs on its own, ahead of the routing, with kernels of its own for those chores.
+  const bool joint = !two && gather_on_load(D);
+  ScanChores chores;
+  if (joint) {
+    chores.pair = w.offsets_shared;
+    chores.pair_hi = D->T;
+    chores.zero_a = static_cast<int*>(w.scratch_r);
+    chores.zero_b = static_cast<int*>(w.scratch_s);
+    chores.nzero = w.scratch_bytes ? ffn_mfma_counter_ints() : 0;
+  } else {
+    // shared expert on the current-layer representation (Eq. (6)/(7)): independent of routing
+    hipLaunchKernelGGL(set_pair, dim3(1), dim3(64), 0, s_shared, w.offsets_shared, 0, D->T);
+    SCMOE_TRY(launch_status());
+  }
   // Fused output decode: for top-1 routing without coefficient gate or residual, on the MFMA
   // path, the shared expert writes y and the routed GEMM2 adds its gate-weighted rows into
   // y[src_token[r]] (every row is written once, dropped tokens keep SE(x_cur)): no y_perm
@@ -355,9 +375,6 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   se.scratch = w.scratch_bytes ? w.scratch_s : nullptr; se.scratch_bytes = w.scratch_bytes;
   se.y = fused ? y : w.s;
   se.ldy = fused ? ldy : D->d;
-  // One stream and the MFMA path: the shared expert's first GEMM joins the routed experts'
-  // (one launch over E + 1 segments); otherwise the shared expert runs on its own here.
-  const bool joint = !two && gather_on_load(D);
   if (!joint) SCMOE_TRY(expert_ffn_any(se, D->dtype, s_shared));
   if (D->cg_mode != SCMOE_CG_NONE)
     SCMOE_TRY(coef_gate(x_cur, ld_cur, D->dtype, W->W_cg, D->cg_mode, D->T, D->d, w.coef, s_shared));
@@ -367,10 +384,12 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   }
   // routed experts on the preceding-layer representation
   if (fused) {
-    SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, y, ldy, two ? ev->join : nullptr, joint ? &se : nullptr));
+    SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, y, ldy, two ? ev->join : nullptr, joint ? &se : nullptr,
+                           joint ? &chores : nullptr));
     return copy_routing(D, w, routing, sm);
   }
-  SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, nullptr, 0, nullptr, joint ? &se : nullptr));
+  SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, nullptr, 0, nullptr, joint ? &se : nullptr,
+                         joint ? &chores : nullptr));
   if (two) {
     hipError_t e = hipStreamWaitEvent(sm, ev->join, 0);
     if (e != hipSuccess) return hip_fail(e);
@@ -445,7 +464,7 @@ extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_pr
   const bool gol = gather_on_load(D);
   SCMOE_TRY(dispatch(x_prev, ld_prev, D->dtype, w.expert_idx, D->T, D->d, E, D->k, D->capacity, w.counts,
                      w.offsets, w.dst_row, w.src_token, gol ? nullptr : w.x_perm, D->d, w.disp_ws,
-                     w.disp_bytes, sm));
+                     w.disp_bytes, sm, nullptr));
   hipError_t he = hipMemcpyAsync(host_plan, w.counts, static_cast<size_t>(E) * 4, hipMemcpyDeviceToHost, sm);
   if (he != hipSuccess) return hip_fail(he);
   EventPair* ev = nullptr;
