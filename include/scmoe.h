@@ -118,9 +118,11 @@ const char* scmoe_status_string(int status);
 int scmoe_last_hip_error(void);
 
 /* Tuning knob, process-wide: tile configuration of the bf16 grouped GEMM behind
- * scmoe_expert_ffn and the layer calls.  0 = 256x256x64 tiles, 8 waves, 2 LDS stages
- * (default); 1 = 256x256x32, 8 waves, 4 stages.  Results agree to bf16 rounding of the same
- * fp32 sums; only speed differs.  Other values give SCMOE_ERR_ARG. */
+ * scmoe_expert_ffn and the layer calls.  0 (default) = chosen per launch: 256x256x64 tiles,
+ * 8 waves, 2 LDS stages, or 128x128x32 tiles, 2 waves, when the larger tiles would not give
+ * every compute unit one; 1 = always 256x256x32, 8 waves, 4 stages; 2 = always 128x128x32.
+ * Results agree to bf16 rounding of the same fp32 sums; only speed differs.  Other values
+ * give SCMOE_ERR_ARG. */
 int scmoe_set_gemm_variant(int32_t variant);
 
 /* Row stride (in elements) that staggers the rows of a GEMM operand of `width` columns:

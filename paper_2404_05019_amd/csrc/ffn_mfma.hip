@@ -461,10 +461,14 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 
 using CfgA = TileCfg<256, 256, 64, 2, 4, 2>;   // 8 waves, 128 KiB LDS, one workgroup per CU
 using CfgB = TileCfg<256, 256, 32, 2, 4, 4>;   // 8 waves, 4 stages, 128 KiB LDS
+#ifndef SCMOE_SMALL_TILES
+#define SCMOE_SMALL_TILES 4      // in quarters of the CU count
+#endif
+using CfgS = TileCfg<128, 128, 32, 1, 2, 2>;   // 2 waves, 40 KiB LDS, four workgroups per CU: small problems
 
 // Tile configuration in use: set by scmoe_set_gemm_variant, else SCMOE_GEMM_VARIANT, else 0.
 static int g_variant = -1;
-constexpr int NUM_VARIANTS = 2;
+constexpr int NUM_VARIANTS = 3;
 
 static int gemm_variant() {
   if (g_variant < 0) {
@@ -526,8 +530,15 @@ template <bool ACT>
 static int launch_variant(const GemmArgs& a, int max_rows, int64_t a_rows, hipStream_t stream) {
   switch (gemm_variant()) {
     case 1: return launch_gemm<CfgB, ACT>(a, max_rows, a_rows, stream);
-    default: return launch_gemm<CfgA, ACT>(a, max_rows, a_rows, stream);
+    case 2: return launch_gemm<CfgS, ACT>(a, max_rows, a_rows, stream);
+    default: break;
   }
+  // Variant 0 picks by size: a problem whose 256 x 256 tiles would not give every CU one is
+  // cut into 128 x 128 tiles instead (four small workgroups per CU).
+  const int64_t tiles = (static_cast<int64_t>(max_rows) / CfgA::BM + a.E + (a.xrows + CfgA::BM - 1) / CfgA::BM) *
+                        ((a.N + CfgA::BN - 1) / CfgA::BN);
+  if (tiles < SCMOE_SMALL_TILES * num_cus() / 4) return launch_gemm<CfgS, ACT>(a, max_rows, a_rows, stream);
+  return launch_gemm<CfgA, ACT>(a, max_rows, a_rows, stream);
 }
 
 __global__ void zero_ints(int* p, int n) {

@@ -238,7 +238,7 @@ def test_expert_ffn_random_segments(oracle, seed):
     E = int(rng.integers(1, 11))
     lens = [int(v) for v in rng.integers(0, 701, E) * (rng.random(E) > 0.2)]
     d, F = 64 * int(rng.integers(1, 9)), 64 * int(rng.integers(1, 13))
-    B.scmoe_set_gemm_variant(seed % 2)
+    B.scmoe_set_gemm_variant(seed % 3)
     try:
         _ffn_case(oracle, E, lens, d, F, "bf16", bool(rng.integers(0, 2)), int(rng.integers(0, 2)),
                   extra_rows=int(rng.integers(0, 9)), pad=bool(rng.integers(0, 2)),
@@ -247,7 +247,7 @@ def test_expert_ffn_random_segments(oracle, seed):
         B.scmoe_set_gemm_variant(0)
 
 
-@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("variant", [0, 1, 2])
 def test_expert_ffn_split_k_tail(oracle, variant):
     """With a workspace the last, partly filled round of tiles is cut along K (here: 3 tiles
     left on one XCD, 1 on another).  Same bar; identical from run to run; the workspace may
@@ -264,7 +264,7 @@ def test_expert_ffn_split_k_tail(oracle, variant):
         B.scmoe_set_gemm_variant(0)
 
 
-@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("variant", [0, 1, 2])
 def test_expert_ffn_tile_variants(oracle, variant):
     """Every tile configuration of the MFMA grouped GEMM meets the same bar."""
     B.scmoe_set_gemm_variant(variant)
