@@ -235,9 +235,10 @@ int scmoe_dispatch(const void* x, int64_t ldx, int32_t dtype, const int32_t* exp
  * identical; they may differ in the last bit from a call without workspace).  NULL, or
  * fewer bytes than asked for: that round runs unsplit.  Calls that may overlap in time
  * need separate workspaces.
- * max_rows <= 32 (a decode step; bf16, d and F multiples of 64): the call is bound by reading
- * the weights, and a weight-streaming kernel replaces the tiled one; with a workspace it cuts
- * K into parts so that the whole chip streams (parts summed in a fixed order).
+ * max_rows <= 64, or max_rows <= 16 E (decode steps; bf16, d and F multiples of 64): the call
+ * is bound by reading the weights, and a weight-streaming kernel replaces the tiled one; up to
+ * 64 rows and with a workspace it cuts K into parts so that the whole chip streams (parts
+ * summed in a fixed order).
  * hidden with a row stride of scmoe_padded_ld(F) instead of F is worth about 15 % of the
  * first GEMM when F * 2 bytes is a large power of two.
  * With E = 1 and offsets = {0, T} this is the dense MLP used for the shared expert

@@ -609,8 +609,8 @@ static GemmArgs second_gemm(const FfnArgs& a, const SplitK& sk) {
 int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   if (!ffn_mfma_supported(a.d, a.F)) return SCMOE_ERR_ARG;
   if (a.max_rows <= 0) return SCMOE_OK;
-  if (gemm_skinny_fits(a.max_rows)) {
-    // a handful of rows (a decode step): bound by streaming the weights, not by the matrix cores
+  if (gemm_skinny_fits(a.max_rows, a.E)) {
+    // a handful of rows per expert (a decode step): bound by streaming the weights, not by the matrix cores
     const SplitK none;
     const int st1 = launch_gemm_skinny(first_gemm(a, none), true, a.max_rows, a.scratch, a.scratch_bytes, stream);
     if (st1 != SCMOE_OK) return st1;
@@ -634,7 +634,7 @@ int ffn_mfma_bf16_pair(const FfnArgs& se, const FfnArgs& rt, hipStream_t stream)
     return SCMOE_ERR_ARG;
   if (se.max_rows <= 0) return ffn_mfma_bf16(rt, stream);
   if (rt.max_rows <= 0) return ffn_mfma_bf16(se, stream);
-  if (gemm_skinny_fits(se.max_rows) || gemm_skinny_fits(rt.max_rows)) {
+  if (gemm_skinny_fits(se.max_rows, se.E) || gemm_skinny_fits(rt.max_rows, rt.E)) {
     const int st0 = ffn_mfma_bf16(se, stream);      // the shared expert first: rt may add to its rows
     if (st0 != SCMOE_OK) return st0;
     return ffn_mfma_bf16(rt, stream);

@@ -247,7 +247,7 @@ struct TileSchedule {
 
 // Grouped GEMM for calls of very few rows (ffn_skinny.hip): true if a call with this upper
 // bound on its packed rows is one for it.
-bool gemm_skinny_fits(int max_rows);
+bool gemm_skinny_fits(int max_rows, int E);
 int launch_gemm_skinny(const GemmArgs& a, bool act, int max_rows, void* scratch, size_t scratch_bytes,
                        hipStream_t stream);
 

@@ -209,16 +209,24 @@ def test_expert_ffn_padded_row_strides(oracle, E, lens, d, F, dtype):
     (8, [1] * 8, 192, 448, True, 1, True),
     (2, [17, 15], 1024, 576, True, 0, False),               # two row subtiles, several k chunks
     (3, [16, 0, 16], 256, 1088, False, 0, True),
-    (16, [2, 0, 0, 1, 0, 3, 0, 0, 1, 0, 0, 0, 0, 0, 0, 1], 512, 2048, True, 0, False)])
-def test_expert_ffn_few_rows(oracle, E, lens, d, F, biases, gelu_mode, pad):
-    """Calls of at most 32 rows (a decode step) take the weight-streaming kernel."""
-    _ffn_case(oracle, E, lens, d, F, "bf16", biases, gelu_mode, extra_rows=0, pad=pad)
+    (16, [2, 0, 0, 1, 0, 3, 0, 0, 1, 0, 0, 0, 0, 0, 0, 1], 512, 2048, True, 0, False),
+    (16, [100, 3, 0, 0, 17, 64, 1, 0, 0, 0, 0, 0, 0, 0, 0, 40], 256, 576, True, 0, False),   # 64-row blocks
+    (8, [0, 65, 0, 0, 16, 33, 0, 14], 128, 320, True, 1, True),
+    (64, [5] * 64, 64, 192, False, 0, False),
+    (2, [40, 24], 1024, 576, True, 0, False),               # 33-64 rows in all: 64-row blocks, cut along K
+    (1, [50], 256, 2048, True, 1, True)])
+@pytest.mark.parametrize("workspace", [False, True])
+def test_expert_ffn_few_rows(oracle, E, lens, d, F, biases, gelu_mode, pad, workspace):
+    """Calls of at most 64 rows, or of segments averaging at most 16 rows (decode steps), take
+    the weight-streaming kernel; with a workspace the small ones are cut along K."""
+    _ffn_case(oracle, E, lens, d, F, "bf16", biases, gelu_mode, extra_rows=0, pad=pad, workspace=workspace)
 
 
 @pytest.mark.parametrize("T,E,k,C_,shared,cg,res", [
     (8, 4, 1, 8, True, 0, False), (20, 8, 1, 3, True, 0, False), (1, 2, 1, 1, True, 0, False),
     (16, 4, 2, 32, False, 0, False), (10, 8, 3, 30, False, 0, False), (32, 16, 1, 32, True, 1, True),
-    (12, 4, 2, 5, True, 2, False)])
+    (12, 4, 2, 5, True, 2, False), (100, 8, 1, 100, True, 0, False), (64, 16, 2, 9, False, 0, False),
+    (250, 16, 1, 250, True, 0, False), (48, 8, 1, 48, True, 0, False), (64, 4, 1, 20, True, 1, False)])
 def test_layer_decode_batches(oracle, T, E, k, C_, shared, cg, res):
     """Layers of a few tokens (per-token decoding, Sec. 5.3): every GEMM has at most 32 rows."""
     L = inputs.make_layer(T=T, d=256, F=512, E=E, dtype="bf16", seed=300 + T, biases=True, cg_rows=cg,
