@@ -504,7 +504,17 @@ static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
   a.nt = (a.N + CFG::BN - 1) / CFG::BN;
   int slots = (mtb * a.nt + 7) / 8;                            // tiles per XCD, upper bound
   const int resident = (num_cus() / 8) * CFG::WG_PER_CU;       // workgroups one XCD holds at once
-  if (slots > resident) slots = resident;
+  if (slots > resident) {
+    slots = resident;
+  } else if (a.splitk_part != nullptr) {
+    // Far fewer tiles than workgroups the chip can hold: launch the workgroups anyway, so
+    // that the schedule cuts every tile along K (as many slots as the split-K scratch has room
+    // for).  From a quarter of the capacity on it no longer pays (measured: tiles cut in two
+    // cost the small workload 6 %).
+    const int room = SPLITK_PARTS / 8;
+    const int want = resident < room ? resident : room;
+    if (want >= 4 * slots) slots = want;
+  }
   // the split-K scratch is laid out for 8 * slots partial tiles of this shape
   if (8 * slots > SPLITK_PARTS ||
       static_cast<size_t>(8) * slots * CFG::BM * CFG::BN * 4 > SPLITK_WS_BYTES - SPLITK_COUNT_BYTES) {
