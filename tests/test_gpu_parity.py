@@ -546,14 +546,14 @@ def test_offload_pool_too_small_is_an_error(oracle):
 
 # --------------------------------------------------- full benchmark sizes, sampled rows
 
-def _full_size(oracle, name, n_sample, k=1, shared=True, normalize=0, pad_weights=False):
+def _full_size(oracle, name, n_sample, k=1, shared=True, normalize=0, pad_weights=False, two_streams=False):
     """Routing compared for every token; output rows compared on a seeded sample (the
-    oracle evaluates those tokens one by one)."""
+    oracle evaluates those tokens one by one).  One stream is what bench.py times."""
     L, cfg = inputs.make_config(name)
     T, E = cfg["T"], cfg["E"]
     C_ = inputs.capacity(T, E, k, cfg["cf"])
     D = DevLayer(L, cfg["dtype"], pad_weights)
-    y, r = run_layer(D, k, C_, shared, normalize, two_streams=shared)
+    y, r = run_layer(D, k, C_, shared, normalize, two_streams=two_streams and shared)
     xg = L["x_prev"] if shared else L["x_cur"]
     rr = oracle.route(xg, L, E, k, C_, normalize)
     assert_routing_equal(r, rr)
@@ -590,7 +590,7 @@ def test_full_size_medium_top3_and_scmoe2(oracle):
 
 def test_full_size_skewed(oracle):
     """Zipf(1.2) expert load with capacity factor 1.0: a large share of tokens is dropped."""
-    cfg, r = _full_size(oracle, "skewed", 96)
+    cfg, r = _full_size(oracle, "skewed", 96, two_streams=True)
     kept = int(r["offsets"][-1])
     assert cfg["C"] == 1024 and 0.4 * cfg["T"] < kept < 0.75 * cfg["T"]
     assert (r["counts"][:3] == 1024).all()
@@ -598,6 +598,7 @@ def test_full_size_skewed(oracle):
 
 @pytest.mark.parametrize("pad_weights", [True, False])
 def test_full_size_large(oracle, pad_weights):
-    """The benchmark workload, with dense weight rows (bench.py's default) and padded ones."""
-    cfg, r = _full_size(oracle, "large", 48, pad_weights=pad_weights)
+    """The benchmark workload: dense weight rows on one stream (the configuration bench.py times),
+    and padded rows with the shared expert on a second stream."""
+    cfg, r = _full_size(oracle, "large", 48, pad_weights=pad_weights, two_streams=pad_weights)
     assert cfg["C"] == 2560
