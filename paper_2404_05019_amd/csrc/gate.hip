@@ -75,8 +75,10 @@ __device__ __forceinline__ void route_token(const float* l, int E, int k, int no
   }
 }
 
-// NW waves per workgroup, each owning EPL experts.
-template <int EPL, int NW, bool BF16>
+// NW waves per workgroup, each owning EPL experts; a lane owns TPL tokens (lane, lane + 64),
+// which share every read of W_g: the kernel is bound by LDS bandwidth, and most of that
+// traffic is the waves re-reading their slab of W_g for every 64 tokens.
+template <int EPL, int NW, int TPL, bool BF16>
 __global__ __launch_bounds__(64 * NW) void gate_kernel(
     const unsigned char* __restrict__ x, int64_t ldx, const float* __restrict__ Wg,
     const float* __restrict__ bias, int T, int d, int E, int k, int normalize,
@@ -84,24 +86,27 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
   constexpr int EB = BF16 ? 2 : 4;                 // element bytes
   constexpr int KC = GATE_ROW_BYTES / EB;          // features per tile
   constexpr int GATE_THREADS = 64 * NW;
-  constexpr int GATE_XV = GATE_TOK * 16 / GATE_THREADS;   // 16-byte pieces of x per thread and tile
+  constexpr int TOK = GATE_TOK * TPL;              // tokens per workgroup
+  constexpr int GATE_XV = TOK * 16 / GATE_THREADS; // 16-byte pieces of x per thread and tile
   constexpr int EPAD = NW * EPL;                   // expert columns held in LDS (zero padded)
   constexpr int LGS = EPAD + 1;                    // row stride of the logit exchange buffer
-  __shared__ __attribute__((aligned(16))) unsigned char xs[GATE_TOK * GATE_ROW_STRIDE];
-  constexpr int WS_ELEMS = (KC * EPAD > GATE_TOK * LGS) ? KC * EPAD : GATE_TOK * LGS;
+  __shared__ __attribute__((aligned(16))) unsigned char xs[TOK * GATE_ROW_STRIDE];
+  constexpr int WS_ELEMS = (KC * EPAD > TOK * LGS) ? KC * EPAD : TOK * LGS;
   __shared__ __attribute__((aligned(16))) float ws[WS_ELEMS];    // reused for the logits at the end
-  __shared__ float row_max[GATE_TOK];
-  __shared__ float row_sum[GATE_TOK];
+  __shared__ float row_max[TOK];
+  __shared__ float row_sum[TOK];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int e0 = wave * EPL;
-  const int t0 = blockIdx.x * GATE_TOK;
+  const int t0 = blockIdx.x * TOK;
 
-  float acc[EPL];
+  float acc[TPL][EPL];
 #pragma unroll
-  for (int j = 0; j < EPL; ++j) acc[j] = 0.0f;
+  for (int tp = 0; tp < TPL; ++tp)
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) acc[tp][j] = 0.0f;
 
   // this thread's pieces of the x tile: piece c = tid + u*256 -> row c/16, 16-byte column c%16
   // The prefetched pieces are four named registers, not an array: as an array written under
@@ -180,17 +185,24 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
       const unsigned char* myrow = xs + lane * GATE_ROW_STRIDE;
       constexpr int XPV = 16 / EB;                 // features per 16-byte piece
       for (int c = 0; c < nvec; ++c) {
-        const uint4 v = *reinterpret_cast<const uint4*>(myrow + c * 16);
-        const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+        uint32_t wd[TPL][4];
+#pragma unroll
+        for (int tp = 0; tp < TPL; ++tp) {
+          const uint4 v = *reinterpret_cast<const uint4*>(myrow + tp * (GATE_TOK * GATE_ROW_STRIDE) + c * 16);
+          wd[tp][0] = v.x; wd[tp][1] = v.y; wd[tp][2] = v.z; wd[tp][3] = v.w;
+        }
         const float* wrow = ws + (c * XPV) * EPAD + e0;
 #pragma unroll
         for (int q = 0; q < XPV; ++q) {
-          float xv;
-          if (BF16) {
-            const uint32_t word = wd[q >> 1];
-            xv = __uint_as_float((q & 1) ? (word & 0xffff0000u) : (word << 16));
-          } else {
-            xv = __uint_as_float(wd[q]);
+          float xv[TPL];
+#pragma unroll
+          for (int tp = 0; tp < TPL; ++tp) {
+            if (BF16) {
+              const uint32_t word = wd[tp][q >> 1];
+              xv[tp] = __uint_as_float((q & 1) ? (word & 0xffff0000u) : (word << 16));
+            } else {
+              xv[tp] = __uint_as_float(wd[tp][q]);
+            }
           }
           float wv[EPL];
           if (EPL >= 4) {
@@ -207,7 +219,9 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
             for (int j = 0; j < EPL; ++j) wv[j] = wrow[q * EPAD + j];
           }
 #pragma unroll
-          for (int j = 0; j < EPL; ++j) acc[j] = __fmaf_rn(xv, wv[j], acc[j]);
+          for (int tp = 0; tp < TPL; ++tp)
+#pragma unroll
+            for (int j = 0; j < EPL; ++j) acc[tp][j] = __fmaf_rn(xv[tp], wv[j], acc[tp][j]);
         }
       }
     }
@@ -215,21 +229,25 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
   __syncthreads();                                 // ws is free: reuse it for the logits
   float* lg = ws;
 #pragma unroll
-  for (int j = 0; j < EPL; ++j) {
-    if (e0 + j < E) {
-      float v = acc[j];
-      if (bias != nullptr) v = __fadd_rn(v, bias[e0 + j]);
-      lg[lane * LGS + e0 + j] = v;
+  for (int tp = 0; tp < TPL; ++tp) {
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) {
+      if (e0 + j < E) {
+        float v = acc[tp][j];
+        if (bias != nullptr) v = __fadd_rn(v, bias[e0 + j]);
+        lg[(tp * GATE_TOK + lane) * LGS + e0 + j] = v;
+      }
     }
   }
   __syncthreads();
 
-  if (wave == 0)
-    route_token(lg + lane * LGS, E, k, normalize, t0 + lane < T, t0 + lane, expert_idx, gate_w, row_max[lane],
-                row_sum[lane]);
+  if (wave < TPL) {                                // wave w routes tokens 64 w .. 64 w + 63 of the workgroup
+    const int tl = wave * GATE_TOK + lane;
+    route_token(lg + tl * LGS, E, k, normalize, t0 + tl < T, t0 + tl, expert_idx, gate_w, row_max[tl], row_sum[tl]);
+  }
   if (probs != nullptr) {
     __syncthreads();
-    const int ntok = (T - t0 < GATE_TOK) ? T - t0 : GATE_TOK;
+    const int ntok = (T - t0 < TOK) ? T - t0 : TOK;
     for (int c = tid; c < ntok * E; c += GATE_THREADS) {
       const int tok = c / E, e = c - tok * E;
       probs[static_cast<int64_t>(t0) * E + c] = expf(lg[tok * LGS + e] - row_max[tok]) / row_sum[tok];
@@ -336,17 +354,17 @@ __global__ __launch_bounds__(256) void gate_small_kernel(
 
 constexpr int GATE_SMALL_LANES = 65536;   // T * EPAD up to which the kernel above is used (256 workgroups: one per CU)
 
-template <int EPL, int NW>
+template <int EPL, int NW, int TPL>
 static void launch_gate(int dtype, const void* x, int64_t ldx, const float* Wg, const float* bias,
                         int T, int d, int E, int k, int normalize, int32_t* idx, float* gw,
                         float* probs, hipStream_t stream) {
-  dim3 grid((T + GATE_TOK - 1) / GATE_TOK), block(64 * NW);
+  dim3 grid((T + GATE_TOK * TPL - 1) / (GATE_TOK * TPL)), block(64 * NW);
   const unsigned char* xb = static_cast<const unsigned char*>(x);
   if (dtype == SCMOE_BF16)
-    hipLaunchKernelGGL((gate_kernel<EPL, NW, true>), grid, block, 0, stream, xb, ldx, Wg, bias, T, d, E, k,
+    hipLaunchKernelGGL((gate_kernel<EPL, NW, TPL, true>), grid, block, 0, stream, xb, ldx, Wg, bias, T, d, E, k,
                        normalize, idx, gw, probs);
   else
-    hipLaunchKernelGGL((gate_kernel<EPL, NW, false>), grid, block, 0, stream, xb, ldx, Wg, bias, T, d, E, k,
+    hipLaunchKernelGGL((gate_kernel<EPL, NW, TPL, false>), grid, block, 0, stream, xb, ldx, Wg, bias, T, d, E, k,
                        normalize, idx, gw, probs);
 }
 
@@ -388,12 +406,14 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
   // Eight waves per workgroup, each with an eighth of the experts (measured against four waves
   // with twice the experts each, bf16: E = 16, T = 32768: 107 -> 89 us; E = 16, T = 16384:
   // 51 -> 35 us; E = 8, T = 8192: 12.7 -> 8.8 us).
-#define SCMOE_GATE(EPL, NW) launch_gate<EPL, NW>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)
-  if (E <= 4) SCMOE_GATE(1, 4);
-  else if (E <= 8) SCMOE_GATE(1, 8);
-  else if (E <= 16) SCMOE_GATE(2, 8);
-  else if (E <= 32) SCMOE_GATE(4, 8);
-  else SCMOE_GATE(8, 8);
+  // Two tokens per lane once that still leaves every CU a workgroup of 128 tokens.
+#define SCMOE_GATE(EPL, NW, TPL) launch_gate<EPL, NW, TPL>(dtype, x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)
+  const bool two = static_cast<int64_t>(T) >= static_cast<int64_t>(2 * GATE_TOK) * num_cus();
+  if (E <= 4) SCMOE_GATE(1, 4, 1);
+  else if (E <= 8) { if (two) SCMOE_GATE(1, 8, 2); else SCMOE_GATE(1, 8, 1); }
+  else if (E <= 16) { if (two) SCMOE_GATE(2, 8, 2); else SCMOE_GATE(2, 8, 1); }
+  else if (E <= 32) { if (two) SCMOE_GATE(4, 8, 2); else SCMOE_GATE(4, 8, 1); }
+  else SCMOE_GATE(8, 8, 1);                        // two tokens per lane would need more than 64 KiB of LDS
 #undef SCMOE_GATE
   return launch_status();
 }

@@ -29,7 +29,8 @@ def _i32(n, fill=None):
     (130, 72, 3, "f32", 2, True), (513, 264, 64, "bf16", 2, False), (64, 8, 1, "bf16", 1, False),
     (4099, 2048, 16, "bf16", 2, True), (300, 128, 33, "f32", 1, True), (1, 16, 2, "f32", 2, False),
     (1500, 256, 8, "bf16", 3, True), (300, 64, 5, "f32", 4, False), (100, 16, 3, "f32", 3, False),
-    (200, 40, 64, "bf16", 4, True)])
+    (200, 40, 64, "bf16", 4, True),
+    (33000, 64, 16, "bf16", 1, True), (32800, 24, 7, "f32", 2, False), (32768, 40, 30, "bf16", 3, True)])   # two tokens per lane
 @pytest.mark.parametrize("normalize", [0, 1])
 def test_gate_parity(oracle, T, d, E, dtype, k, use_bias, normalize):
     rng = np.random.default_rng(T + d + E)
