@@ -291,16 +291,13 @@ __global__ __launch_bounds__(256) void gate_small_kernel(
   for (int c0 = 0; c0 < d; c0 += kch) {
     const int kn = (d - c0 < kch) ? d - c0 : kch;  // multiple of 8
     __syncthreads();                               // the previous chunk has been consumed
-    // rows c0 .. c0 + kn - 1 of W_g are kn * E consecutive floats (a multiple of 8, 32-byte aligned)
-    const float4* wsrc = reinterpret_cast<const float4*>(Wg + static_cast<int64_t>(c0) * E);
-    for (int i = tid; i < kn * E / 4; i += 256) {
-      const float4 w4 = wsrc[i];
-      const float w[4] = {w4.x, w4.y, w4.z, w4.w};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int fl = 4 * i + q, f = fl / E, ee = fl - f * E;   // feature c0 + f, expert ee
-        wsm[ee * wrs + f] = w[q];
-      }
+    // W_g rows c0 .. c0 + kn - 1, transposed: thread (tl, e) copies column e of rows tl, tl + tpw, ...
+    // (consecutive e: coalesced reads; epad is a power of two, so no division by E is needed)
+    if (e < E) {
+      const float* wsrc = Wg + static_cast<int64_t>(c0) * E + e;
+      float* wdst = wsm + e * wrs;
+#pragma unroll 8
+      for (int f = tl; f < kn; f += tpw) wdst[f] = wsrc[static_cast<int64_t>(f) * E];
     }
     const int vpr = kn * EB / 16;                  // 16-byte pieces per row
     for (int i = tid; i < tpw * vpr; i += 256) {
@@ -382,7 +379,7 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
   // experts per wave (four waves per workgroup)
   int epad = 1;
   while (epad < E) epad <<= 1;
-  if (static_cast<int64_t>(T) * epad <= GATE_SMALL_LANES && aligned16(Wg)) {   // it copies W_g 16 bytes at a time
+  if (static_cast<int64_t>(T) * epad <= GATE_SMALL_LANES) {
     const int tpw = 256 / epad, eb = elem_bytes(dtype);
     // features per chunk: W chunk <= 32 KiB, x chunk <= 28 KiB (60 KiB of dynamic LDS beside
     // the 4 KiB of static arrays), a multiple of 8, no more than d
