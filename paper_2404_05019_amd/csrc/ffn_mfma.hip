@@ -62,6 +62,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   constexpr int KS32 = BK / 32;                                 // 32-k MFMA steps per k-tile
   constexpr int HS = 2 * KS32;                                  // half-steps per k-tile
   constexpr int LPW = CFG::A_PER_WAVE + CFG::B_PER_WAVE;        // direct loads per wave and k-tile
+  constexpr bool XSEG = ACT, DECODE = !ACT;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const int tid = threadIdx.x;
@@ -87,7 +88,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   const unsigned char* abase = nullptr;     // OFF32: p.A / the expert's W, advanced to the item's first k-tile
   const unsigned char* wbase = nullptr;
   auto set_ptrs = [&](int e, int row0, int row_end, int n0, int kb) {   // kb: first k-tile of the item
-    const bool xs = e == p.E;                 // the dense extra segment: operands of its own
+    // The dense extra segment (operands of its own) exists for first GEMMs only, the fused
+    // output decode for second GEMMs only: each instantiation carries one of the two.
+    const bool xs = XSEG && e == p.E;
     const int64_t lda = xs ? p.xlda : p.lda, ldw = xs ? p.xldw : p.ldw;
     const int32_t* gather = xs ? nullptr : p.gather;
     const unsigned char* We = (xs ? p.xW : p.W + static_cast<int64_t>(e) * p.N * ldw * 2) + static_cast<int64_t>(kb) * RB;
@@ -245,8 +248,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     for (int j = 0; j < NJ; ++j) {
       const int n = n0 + wave_n * CFG::TN + j * 16 + 4 * lq;
       f32x4_t b = {0.0f, 0.0f, 0.0f, 0.0f};
-      const float* bias = (e == p.E) ? p.xbias : p.bias + static_cast<int64_t>(e) * p.N;
-      if (((e == p.E) ? p.xbias : p.bias) != nullptr && part <= 0 && n < p.N)
+      const bool xseg = XSEG && e == p.E;
+      const float* bias = xseg ? p.xbias : p.bias + static_cast<int64_t>(e) * p.N;
+      if ((xseg ? p.xbias : p.bias) != nullptr && part <= 0 && n < p.N)
         b = *reinterpret_cast<const f32x4_t*>(bias + n);
 #pragma unroll
       for (int i = 0; i < MI; ++i) acc[i][j] = b;
@@ -325,8 +329,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     const int itn = it + nslots;
     const bool more = itn < sched.nitems;
     const int crow0 = row0, crow_end = row_end, cn0 = n0, cpart = part, cw = it - sched.full;
-    unsigned char* const cC = (e == p.E) ? p.xC : p.C;        // output of the current tile's segment
-    const int64_t cldc = (e == p.E) ? p.xldc : p.ldc;
+    unsigned char* const cC = (XSEG && e == p.E) ? p.xC : p.C;        // output of the current tile's segment
+    const int64_t cldc = (XSEG && e == p.E) ? p.xldc : p.ldc;
     lds_barrier();                    // every wave holds its last fragments: LDS is free
     if (more) {
       setup(itn);
@@ -393,7 +397,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       const int mbase = crow0 + wave_m * CFG::TM + i * 32;
       if (!finish || mbase >= crow_end) continue;   // wave-uniform: not the last part / slab past the segment
       float rscale[2] = {1.0f, 1.0f};             // fused decode: the gate weights of this lane's two rows
-      if (p.scatter) {
+      if (DECODE && p.scatter) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
           const int mr = (mbase + u * 16 + l16 < crow_end) ? mbase + u * 16 + l16 : crow_end - 1;
@@ -416,7 +420,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
               for (int q = 0; q < 4; ++q)
                 v[q] = (p.gelu_mode == SCMOE_GELU_TANH) ? gelu_tanh_fast(v[q]) : gelu_erf_fast(v[q]);
             }
-            if (p.scatter) {
+            if (DECODE && p.scatter) {
 #pragma unroll
               for (int q = 0; q < 4; ++q) v[q] *= rscale[u];
             }
@@ -438,7 +442,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
           const int n = cn0 + wave_n * CFG::TN + c * 8;
           if (m < crow_end && n < p.N) {
             int64_t orow = m;
-            if (p.scatter) {
+            if (DECODE && p.scatter) {
               // output decode: this packed row belongs to token orow; add the row already there
               orow = p.scatter[m];
               const uint4 a = *reinterpret_cast<const uint4*>(p.addend + (orow * p.ldadd + n) * 2);
@@ -499,6 +503,8 @@ static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
     if (err != hipSuccess) return hip_fail(err);
     if (dev >= 0) attr_set[dev].store(true, std::memory_order_release);
   }
+  // a first GEMM (ACT) may carry the dense extra segment, a second one the output decode
+  if (ACT ? (a.scatter != nullptr || a.addend != nullptr) : a.xrows != 0) return SCMOE_ERR_ARG;
   // upper bound on row tiles: sum_e ceil(c_e / BM) <= max_rows / BM + E
   const int mtb = max_rows / CFG::BM + a.E + (a.xrows + CFG::BM - 1) / CFG::BM;
   a.nt = (a.N + CFG::BN - 1) / CFG::BN;
