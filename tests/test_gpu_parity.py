@@ -429,6 +429,26 @@ def test_layer_random_configurations(oracle, seed):
                 two_streams=shared and bool(rng.integers(0, 2)), pad_weights=bool(rng.integers(0, 2)))
 
 
+@pytest.mark.parametrize("seed", range(20))
+def test_layer_random_small_batches(oracle, seed):
+    """Seeded sweep over decode-size calls on the MFMA widths: 1 to 300 tokens, 1 to 64 experts,
+    k up to 4: the few-row GEMM in its three forms (32-row and 64-row blocks, cut along K or
+    not), the per-chain gate, the tiled GEMM with 128-row tiles and forced split-K."""
+    rng = np.random.default_rng(8000 + seed)
+    T = int(rng.choice([1, 2, 7, 16, 31, 32, 33, 48, 64, 65, 100, 129, 200, 300]))
+    E = int(rng.choice([1, 2, 3, 8, 16, 40, 64]))
+    k = int(rng.integers(1, min(E, 4) + 1))
+    d, F = 64 * int(rng.integers(1, 6)), 64 * int(rng.integers(1, 10))
+    shared = bool(rng.integers(0, 2))
+    cg = int(rng.integers(0, 3)) if shared else 0
+    C_ = int(rng.choice([1, max(1, T * k // (2 * E)), -(-T * k // E), T * k]))
+    L = inputs.make_layer(T=T, d=d, F=F, E=E, dtype="bf16", seed=8100 + seed, biases=bool(rng.integers(0, 2)),
+                          cg_rows=cg, w_scale=0.05)
+    _layer_case(oracle, L, "bf16", E, k, C_, shared, normalize=int(rng.integers(0, 2)), cg_mode=cg,
+                gelu_mode=int(rng.integers(0, 2)), residual=shared and bool(rng.integers(0, 2)),
+                two_streams=shared and bool(rng.integers(0, 2)), pad_weights=bool(rng.integers(0, 2)))
+
+
 @pytest.mark.parametrize("two_streams", [False, True])
 def test_layer_in_a_hip_graph(oracle, two_streams):
     """The layer call makes no host synchronisation, allocates nothing and clears its
