@@ -165,8 +165,12 @@ struct TileSchedule {
   int mt_seg, nt, E, xt, xrows;   // row tiles of the offsets[] segments / of the extra segment
   const int32_t* offsets;
   int nslots;
-  int a0, na, b0;                 // this XCD's share: tiles a0 .. a0+na-1 of the extra segment's
-                                  // range, then tiles from b0 on of the other range
+  int a0, na, rr, b0;             // this XCD's share: tiles a0 .. a0+na-1 of the extra segment's
+                                  // range; of the other range rr tiles dealt out in chunks of
+                                  // RR tiles, XCD after XCD (all XCDs then work on the same one
+                                  // or two experts' weights at a time, which the memory-side
+                                  // cache holds), then tiles from b0 on of the undealt rest
+  static constexpr int RR = 32;
   // Work items of this XCD: its `full` tiles that fill whole rounds of nslots workgroups, then
   // the `rem` tiles of the last round, each cut along K into S parts so that the round keeps
   // (nearly) all workgroups busy.  Item it < full is local tile it; item full + w is part
@@ -185,7 +189,11 @@ struct TileSchedule {
       return last > first ? last - first : 0;
     };
     na = share(xt * nt, a0);
-    const int n = na + share(mt_seg * nt, b0);
+    const int routed = mt_seg * nt;
+    rr = (routed / (8 * RR)) * RR;
+    int n = share(routed - 8 * rr, b0);
+    b0 += 8 * rr;
+    n += na + rr;
     full = (n / nslots) * nslots;
     rem = n - full;
     S = 1;
@@ -227,19 +235,24 @@ struct TileSchedule {
       row_end = xrows;
       return;
     }
-    raster(b0 + l - na, mt_seg, mt, n0);
+    // Segment after segment, each in its own raster order: a raster group never holds rows
+    // of two experts, so the workgroups that run side by side share one expert's weights.
+    int t = l - na;
+    t = (t < rr) ? ((t / RR) * 8 + xcd) * RR + t % RR : b0 + t - rr;
     row0 = 0;
     row_end = 1;
+    n0 = 0;
     for (e = 0; e < E; ++e) {
       const int s = offsets[e];
       const int c = offsets[e + 1] - s;
       const int ntile = (c + BM - 1) / BM;
-      if (mt < ntile) {
+      if (t < ntile * nt) {
+        raster(t, ntile, mt, n0);
         row0 = s + mt * BM;
         row_end = s + c;
         break;
       }
-      mt -= ntile;
+      t -= ntile * nt;
     }
     if (e == E) e = E - 1;   // not reachable for a tile of this XCD's share
   }
