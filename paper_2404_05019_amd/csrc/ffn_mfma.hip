@@ -48,7 +48,7 @@ struct TileCfg {
   static constexpr int LDS_BYTES = NS * STAGE + WAVES * STG_BYTES;
   // workgroups of this shape that fit one CU (512 VGPRs per SIMD lane, 160 KiB LDS)
   static constexpr int WG_PER_CU = (160 * 1024 / LDS_BYTES) < (8 / WAVES) ? (160 * 1024 / LDS_BYTES) : (8 / WAVES);
-  static constexpr int GM = 4;                           // row tiles per raster group
+  static constexpr int GM = 6;                           // row tiles per raster group
   static_assert(BM % (RPL * WAVES) == 0 && BN % (RPL * WAVES) == 0, "loads must divide evenly");
   static_assert(TM == 128 && TN == 64 && (BK == 32 || BK == 64) && NS >= 2 && NS <= 4, "tile shape");
   static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024 && WG_PER_CU >= 1, "LDS budget");

@@ -155,21 +155,23 @@ __device__ __forceinline__ void lds_barrier() {
 
 // Persistent tile schedule.  Row tiles are counted from offsets[] on the device (no host
 // round trip).  Workgroup ids congruent mod 8 run on one XCD.  The tiles form up to two
-// ranges, each in the raster order "GM row tiles x all column tiles": the dense extra
-// segment (if any) and the E segments of offsets[].  XCD x owns the x-th eighth of each range
-// (so every XCD gets the same mix of the two kinds of work), and its workgroups take the
-// tiles of its share round-robin, so the tiles in flight on one XCD are neighbours and
-// share A and W panels in its L2.
+// ranges: the dense extra segment (if any) and the E segments of offsets[], segment after
+// segment, each segment in the raster order "a group of up to GM row tiles x all column
+// tiles" (so a group never mixes two experts' weights).  XCD x owns the x-th eighth of the
+// extra segment's range; the other range is dealt to the XCDs in chunks of RR tiles, XCD
+// after XCD, and only the rest that does not fill a round of chunks is cut into eighths (so
+// every XCD gets the same amount of both kinds of work, and at any time all XCDs read the
+// weights of the same one or two experts, which the memory-side cache then serves).  The
+// workgroups of an XCD take the tiles of its share round-robin, so the tiles in flight on one
+// XCD are neighbours and share A and W panels in its L2.
 template <int BM, int BN, int GM>
 struct TileSchedule {
   int mt_seg, nt, E, xt, xrows;   // row tiles of the offsets[] segments / of the extra segment
   const int32_t* offsets;
   int nslots;
   int a0, na, rr, b0;             // this XCD's share: tiles a0 .. a0+na-1 of the extra segment's
-                                  // range; of the other range rr tiles dealt out in chunks of
-                                  // RR tiles, XCD after XCD (all XCDs then work on the same one
-                                  // or two experts' weights at a time, which the memory-side
-                                  // cache holds), then tiles from b0 on of the undealt rest
+                                  // range; of the other range rr tiles out of the dealt chunks,
+                                  // then tiles from b0 on of the undealt rest
   static constexpr int RR = 32;
   // Work items of this XCD: its `full` tiles that fill whole rounds of nslots workgroups, then
   // the `rem` tiles of the last round, each cut along K into S parts so that the round keeps
@@ -217,11 +219,25 @@ struct TileSchedule {
     }
   }
   // raster order inside a range of mt row tiles: tile l -> row tile, first column
+  // (the fewest groups of at most GM row tiles, of sizes that differ by one at most: the first
+  // `big` groups have one row tile more than the others)
   __device__ __forceinline__ void raster(int l, int mt, int& m, int& n0) const {
-    const int grp = l / (GM * nt);
-    const int r = l - grp * GM * nt;
-    const int grows = (mt - grp * GM < GM) ? mt - grp * GM : GM;
-    m = grp * GM + r % grows;
+    const int ng = (mt + GM - 1) / GM;
+    const int base = mt / ng, big = mt - base * ng;
+    const int lbig = big * (base + 1) * nt;          // tiles in the larger groups
+    int grows, first, r;
+    if (l < lbig) {
+      grows = base + 1;
+      const int g = l / (grows * nt);
+      first = g * grows;
+      r = l - g * grows * nt;
+    } else {
+      grows = base;
+      const int g = (l - lbig) / (grows * nt);
+      first = big * (base + 1) + g * grows;
+      r = (l - lbig) - g * grows * nt;
+    }
+    m = first + r % grows;
     n0 = (r / grows) * BN;
   }
   // local tile l -> expert e (E: the dense extra segment), packed rows [row0, row_end)
