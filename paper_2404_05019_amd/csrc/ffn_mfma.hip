@@ -21,8 +21,10 @@
 //  * The MFMA is issued with the weight fragment as its first operand, so a lane ends up
 //    holding 4 consecutive output columns of one row; the epilogue re-assembles rows in a
 //    small per-wave LDS patch and stores whole 128-byte lines.
-//  * Workgroup ids are remapped so that each XCD (ids congruent mod 8 land on one XCD and
-//    share its L2) walks a compact block of neighbouring tiles.
+//  * Workgroup ids congruent mod 8 land on one XCD and share its L2: the tiles in flight on
+//    an XCD are neighbours inside one expert (they share A and W panels), and the XCDs are
+//    dealt neighbouring chunks, so that all of them read the same experts' weights at a time
+//    (TileSchedule).
 //  * Rows can be gathered on load through an index array (the dispatch permutation, paper
 //    Sec. 2.2 "input encode"), and the second GEMM can scatter, scale and add on store
 //    ("output decode"), which lets the layer skip both permuted copies.
