@@ -50,7 +50,10 @@ struct TileCfg {
   static constexpr int LDS_BYTES = NS * STAGE + WAVES * STG_BYTES;
   // workgroups of this shape that fit one CU (512 VGPRs per SIMD lane, 160 KiB LDS)
   static constexpr int WG_PER_CU = (160 * 1024 / LDS_BYTES) < (8 / WAVES) ? (160 * 1024 / LDS_BYTES) : (8 / WAVES);
-  static constexpr int GM = 6;                           // row tiles per raster group
+  // Row tiles per raster group.  A first GEMM (N = F) has many column tiles and an XCD's 32
+  // tiles in flight are best a 6 x 5 patch of a group; a second GEMM (N = d) has few (8 at
+  // d = 2048), and groups of 4 x 8 tiles coincide with the chunks the XCDs are dealt.
+  static constexpr int GM_FIRST = 6, GM_SECOND = 4;
   static_assert(BM % (RPL * WAVES) == 0 && BN % (RPL * WAVES) == 0, "loads must divide evenly");
   static_assert(TM == 128 && TN == 64 && (BK == 32 || BK == 64) && NS >= 2 && NS <= 4, "tile shape");
   static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024 && WG_PER_CU >= 1, "LDS budget");
@@ -73,7 +76,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 
   // ---- tile schedule ------------------------------------------------------------------------
   const int nk_all = p.Kd / BK;
-  const TileSchedule<BM, BN, CFG::GM> sched(p, nk_all, p.splitk_part != nullptr);
+  const TileSchedule<BM, BN, ACT ? CFG::GM_FIRST : CFG::GM_SECOND> sched(p, nk_all, p.splitk_part != nullptr);
   const int nslots = sched.nslots;
   int it = blockIdx.x >> 3;                // work item: a tile, or one K-part of a tile of the last round
   if (it >= sched.nitems) return;
