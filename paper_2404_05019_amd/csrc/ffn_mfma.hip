@@ -59,7 +59,7 @@ struct TileCfg {
   static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024 && WG_PER_CU >= 1, "LDS budget");
 };
 
-template <class CFG, bool ACT, bool OFF32>
+template <class CFG, bool ACT, bool OFF32, bool DEC>
 __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void gemm_bf16_kernel(const GemmArgs p) {
   constexpr int BM = CFG::BM, BN = CFG::BN, BK = CFG::BK, RB = CFG::RB, CPR = CFG::CPR;
   constexpr int MI = CFG::MI, NJ = CFG::NJ, STAGE = CFG::STAGE, A_BYTES = CFG::A_BYTES;
@@ -67,7 +67,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   constexpr int KS32 = BK / 32;                                 // 32-k MFMA steps per k-tile
   constexpr int HS = 2 * KS32;                                  // half-steps per k-tile
   constexpr int LPW = CFG::A_PER_WAVE + CFG::B_PER_WAVE;        // direct loads per wave and k-tile
-  constexpr bool XSEG = ACT, DECODE = !ACT;
+  constexpr bool XSEG = ACT, DECODE = DEC;
+  static_assert(!(ACT && DEC), "the output decode belongs to second GEMMs");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const int tid = threadIdx.x;
@@ -94,7 +95,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   const unsigned char* wbase = nullptr;
   auto set_ptrs = [&](int e, int row0, int row_end, int n0, int kb) {   // kb: first k-tile of the item
     // The dense extra segment (operands of its own) exists for first GEMMs only, the fused
-    // output decode for second GEMMs only: each instantiation carries one of the two.
+    // output decode for second GEMMs only and in an instantiation of its own: no kernel
+    // carries code it does not run (the register allocation of the k loop feels every
+    // scalar that is live across it).
     const bool xs = XSEG && e == p.E;
     const int64_t lda = xs ? p.xlda : p.lda, ldw = xs ? p.xldw : p.ldw;
     const int32_t* gather = xs ? nullptr : p.gather;
@@ -337,6 +340,40 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     unsigned char* const cC = (XSEG && e == p.E) ? p.xC : p.C;        // output of the current tile's segment
     const int64_t cldc = (XSEG && e == p.E) ? p.xldc : p.ldc;
     lds_barrier();                    // every wave holds its last fragments: LDS is free
+    // Fused output decode: everything the epilogue needs from memory is requested here, ahead
+    // of the next tile's first k-tiles (loads complete in issue order, and the epilogue has
+    // nothing to overlap a round trip with): the token of each of the wave's 128 packed rows
+    // (lane l: rows l and 64 + l; other lanes get them by a lane permute), their gate
+    // weights, and the 16-byte pieces of the first slab's output rows that this lane will
+    // add to (each slab then requests the next one's before it does its own work).
+    constexpr int SLABS = MI / 2, PIECES = 32 / 8;     // 32-row slabs; a store instruction covers 8 rows
+    int dtok[2] = {0, 0};
+    float dscale[2] = {1.0f, 1.0f};
+    uint4 dadd[PIECES];
+    auto addend_loads = [&](int i) {                   // slab i's pieces of the rows to add to
+      const int n = cn0 + wave_n * CFG::TN + (lane & 7) * 8;
+#pragma unroll
+      for (int g = 0; g < PIECES; ++g) {
+        const int tok = __shfl(dtok[i >> 1], (i & 1) * 32 + g * 8 + (lane >> 3));
+        dadd[g] = make_uint4(0u, 0u, 0u, 0u);
+        if (n < p.N) dadd[g] = *reinterpret_cast<const uint4*>(p.addend + (static_cast<int64_t>(tok) * p.ldadd + n) * 2);
+      }
+    };
+    auto decode_loads = [&]() {
+      if constexpr (DECODE) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          int r = crow0 + wave_m * CFG::TM + q * 64 + lane;
+          if (r > crow_end - 1) r = crow_end - 1;      // rows past the segment: its last row (never stored)
+          dtok[q] = p.scatter[r];
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) dscale[q] = p.row_scale[dtok[q]];
+        addend_loads(0);
+      }
+    };
+    constexpr bool dec = DECODE;
+    if (dec && cpart < 0) decode_loads();
     if (more) {
       setup(itn);
       issue_prologue();
@@ -388,6 +425,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
             for (int j = 0; j < NJ; ++j) acc[i][j] = (q == 0) ? t[j] : acc[i][j] + t[j];
           }
         }
+        if (dec) decode_loads();
       }
     }
 
@@ -402,12 +440,13 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       const int mbase = crow0 + wave_m * CFG::TM + i * 32;
       if (!finish || mbase >= crow_end) continue;   // wave-uniform: not the last part / slab past the segment
       float rscale[2] = {1.0f, 1.0f};             // fused decode: the gate weights of this lane's two rows
-      if (DECODE && p.scatter) {
+      uint4 add_cur[PIECES];
+      if (dec) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int mr = (mbase + u * 16 + l16 < crow_end) ? mbase + u * 16 + l16 : crow_end - 1;
-          rscale[u] = p.row_scale[p.scatter[mr]];
-        }
+        for (int u = 0; u < 2; ++u) rscale[u] = __shfl(dscale[i >> 1], (i & 1) * 32 + u * 16 + l16);
+#pragma unroll
+        for (int g = 0; g < PIECES; ++g) add_cur[g] = dadd[g];
+        if (i + 1 < SLABS) addend_loads(i + 1);
       }
 #pragma unroll
       for (int h = 0; h < 32 / CFG::STG_ROWS; ++h) {
@@ -425,7 +464,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
               for (int q = 0; q < 4; ++q)
                 v[q] = (p.gelu_mode == SCMOE_GELU_TANH) ? gelu_tanh_fast(v[q]) : gelu_erf_fast(v[q]);
             }
-            if (DECODE && p.scatter) {
+            if (dec) {
 #pragma unroll
               for (int q = 0; q < 4; ++q) v[q] *= rscale[u];
             }
@@ -445,12 +484,13 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
           uint4 o = *reinterpret_cast<const uint4*>(stg + r * CFG::STG_ROW + ((c ^ swz<8>(r)) << 4));
           const int m = mbase + h * CFG::STG_ROWS + r;
           const int n = cn0 + wave_n * CFG::TN + c * 8;
+          const int g = (h * CFG::STG_ROWS + r0) / 8;          // which of the slab's 8-row pieces
+          int64_t orow = m;
+          if (dec) orow = __shfl(dtok[i >> 1], (i & 1) * 32 + g * 8 + (lane >> 3));   // (all lanes take part)
           if (m < crow_end && n < p.N) {
-            int64_t orow = m;
-            if (DECODE && p.scatter) {
+            if (dec) {
               // output decode: this packed row belongs to token orow; add the row already there
-              orow = p.scatter[m];
-              const uint4 a = *reinterpret_cast<const uint4*>(p.addend + (orow * p.ldadd + n) * 2);
+              const uint4 a = add_cur[g];
               o.x = add_bf16x2(o.x, a.x);
               o.y = add_bf16x2(o.y, a.y);
               o.z = add_bf16x2(o.z, a.z);
@@ -496,20 +536,21 @@ int set_gemm_variant(int v) {
 
 bool ffn_mfma_supported(int d, int F) { return d > 0 && F > 0 && (d % 64) == 0 && (F % 64) == 0; }
 
-template <class CFG, bool ACT, bool OFF32>
+template <class CFG, bool ACT, bool OFF32, bool DEC>
 static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
   // the dynamic-LDS limit is a per-device attribute of the kernel: raise it once per device
   static std::atomic<bool> attr_set[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
   if (dev < 0 || !attr_set[dev].load(std::memory_order_acquire)) {
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<CFG, ACT, OFF32>),
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<CFG, ACT, OFF32, DEC>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, CFG::LDS_BYTES);
     if (err != hipSuccess) return hip_fail(err);
     if (dev >= 0) attr_set[dev].store(true, std::memory_order_release);
   }
-  // a first GEMM (ACT) may carry the dense extra segment, a second one the output decode
+  // a first GEMM (ACT) may carry the dense extra segment, a second one the output decode (DEC)
   if (ACT ? (a.scatter != nullptr || a.addend != nullptr) : a.xrows != 0) return SCMOE_ERR_ARG;
+  if (DEC != (a.scatter != nullptr) || (DEC && (a.addend == nullptr || a.row_scale == nullptr))) return SCMOE_ERR_ARG;
   // upper bound on row tiles: sum_e ceil(c_e / BM) <= max_rows / BM + E
   const int mtb = max_rows / CFG::BM + a.E + (a.xrows + CFG::BM - 1) / CFG::BM;
   a.nt = (a.N + CFG::BN - 1) / CFG::BN;
@@ -532,7 +573,7 @@ static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
     a.splitk_part = nullptr;
     a.splitk_count = nullptr;
   }
-  hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT, OFF32>), dim3(8 * slots), dim3(CFG::THREADS), CFG::LDS_BYTES,
+  hipLaunchKernelGGL((gemm_bf16_kernel<CFG, ACT, OFF32, DEC>), dim3(8 * slots), dim3(CFG::THREADS), CFG::LDS_BYTES,
                      stream, a);
   return launch_status();
 }
@@ -543,8 +584,13 @@ static int launch_gemm(const GemmArgs& a, int max_rows, int64_t a_rows, hipStrea
   const int64_t lim = int64_t(1) << 32;
   const bool off32 = a_rows * a.lda * 2 < lim && static_cast<int64_t>(a.N) * a.ldw * 2 < lim &&
                      static_cast<int64_t>(a.xrows) * a.xlda * 2 < lim && static_cast<int64_t>(a.N) * a.xldw * 2 < lim;
-  return off32 ? launch_gemm_impl<CFG, ACT, true>(a, max_rows, stream)
-               : launch_gemm_impl<CFG, ACT, false>(a, max_rows, stream);
+  if constexpr (!ACT) {
+    if (a.scatter != nullptr)
+      return off32 ? launch_gemm_impl<CFG, ACT, true, true>(a, max_rows, stream)
+                   : launch_gemm_impl<CFG, ACT, false, true>(a, max_rows, stream);
+  }
+  return off32 ? launch_gemm_impl<CFG, ACT, true, false>(a, max_rows, stream)
+               : launch_gemm_impl<CFG, ACT, false, false>(a, max_rows, stream);
 }
 
 template <bool ACT>
