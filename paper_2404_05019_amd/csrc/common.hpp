@@ -89,8 +89,12 @@ struct FfnArgs {
   void* hidden; int64_t ldh;       // [rows, F] scratch
   void* y; int64_t ldy;            // [rows, d]
   int gelu_mode;
-  // Fused output decode of the second GEMM (MFMA path only; scatter == nullptr: off):
+  // Fused output decode of the second GEMM (MFMA path only; all three pointers nullptr: off).
+  // With scatter:
   //   y[scatter[r], :] = addend[scatter[r], :] + row_scale[scatter[r]] * (W2 . hidden[r] + b2)
+  // Without scatter (rows stay in place; tiled kernel only, not the few-row one), row_scale
+  // holding PAIRS of coefficients per row of which the first is used, either pointer optional:
+  //   y[r, :] = addend[r, :] + row_scale[2 r] * (W2 . hidden[r] + b2)
   const int32_t* scatter; const float* row_scale; const void* addend; int64_t ldadd;
   // Scratch of the MFMA path (split-K of the last round of tiles); may be nullptr: no split.
   void* scratch; size_t scratch_bytes;
@@ -112,6 +116,7 @@ inline int64_t padded_ld(int64_t width, int dtype) {
   return ((width * eb) % 512 == 0) ? width + 128 / eb : width;
 }
 bool ffn_mfma_supported(int d, int F);
+bool gemm_skinny_fits(int max_rows, int E);   // the MFMA path would take its few-row kernel for such a call
 size_t ffn_mfma_scratch_bytes();   // scratch the MFMA path can use (16-byte aligned)
 int ffn_mfma_counter_ints();       // ints at the start of that scratch that must be zero before a call
 

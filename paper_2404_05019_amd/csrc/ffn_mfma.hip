@@ -59,7 +59,11 @@ struct TileCfg {
   static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024 && WG_PER_CU >= 1, "LDS budget");
 };
 
-template <class CFG, bool ACT, bool OFF32, bool DEC>
+// DEC: output decode in the epilogue of a second GEMM.  0: none.  1: row r of the packed
+// output goes to token scatter[r]: C[scatter[r]] = addend[scatter[r]] + row_scale[scatter[r]] * row.
+// 2: rows stay where they are: C[r] = addend[r] + row_scale[2 r] * row (row_scale: pairs of
+// coefficients per row, the first one is used; either pointer may be null).
+template <class CFG, bool ACT, bool OFF32, int DEC>
 __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void gemm_bf16_kernel(const GemmArgs p) {
   constexpr int BM = CFG::BM, BN = CFG::BN, BK = CFG::BK, RB = CFG::RB, CPR = CFG::CPR;
   constexpr int MI = CFG::MI, NJ = CFG::NJ, STAGE = CFG::STAGE, A_BYTES = CFG::A_BYTES;
@@ -67,8 +71,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
   constexpr int KS32 = BK / 32;                                 // 32-k MFMA steps per k-tile
   constexpr int HS = 2 * KS32;                                  // half-steps per k-tile
   constexpr int LPW = CFG::A_PER_WAVE + CFG::B_PER_WAVE;        // direct loads per wave and k-tile
-  constexpr bool XSEG = ACT, DECODE = DEC;
-  static_assert(!(ACT && DEC), "the output decode belongs to second GEMMs");
+  constexpr bool XSEG = ACT, DECODE = DEC != 0;
+  static_assert(!(ACT && DEC != 0) && DEC >= 0 && DEC <= 2, "the output decode belongs to second GEMMs");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
   const int tid = threadIdx.x;
@@ -356,7 +360,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       for (int g = 0; g < PIECES; ++g) {
         const int tok = __shfl(dtok[i >> 1], (i & 1) * 32 + g * 8 + (lane >> 3));
         dadd[g] = make_uint4(0u, 0u, 0u, 0u);
-        if (n < p.N) dadd[g] = *reinterpret_cast<const uint4*>(p.addend + (static_cast<int64_t>(tok) * p.ldadd + n) * 2);
+        if (n < p.N && (DEC == 1 || p.addend != nullptr))
+          dadd[g] = *reinterpret_cast<const uint4*>(p.addend + (static_cast<int64_t>(tok) * p.ldadd + n) * 2);
       }
     };
     auto decode_loads = [&]() {
@@ -365,10 +370,13 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
         for (int q = 0; q < 2; ++q) {
           int r = crow0 + wave_m * CFG::TM + q * 64 + lane;
           if (r > crow_end - 1) r = crow_end - 1;      // rows past the segment: its last row (never stored)
-          dtok[q] = p.scatter[r];
+          dtok[q] = (DEC == 1) ? p.scatter[r] : r;
         }
 #pragma unroll
-        for (int q = 0; q < 2; ++q) dscale[q] = p.row_scale[dtok[q]];
+        for (int q = 0; q < 2; ++q) {
+          if (DEC == 1) dscale[q] = p.row_scale[dtok[q]];
+          else dscale[q] = p.row_scale ? p.row_scale[2 * static_cast<int64_t>(dtok[q])] : 1.0f;
+        }
         addend_loads(0);
       }
     };
@@ -536,7 +544,12 @@ int set_gemm_variant(int v) {
 
 bool ffn_mfma_supported(int d, int F) { return d > 0 && F > 0 && (d % 64) == 0 && (F % 64) == 0; }
 
-template <class CFG, bool ACT, bool OFF32, bool DEC>
+// which output decode a launch asks for (see gemm_bf16_kernel)
+static int decode_kind(const GemmArgs& a) {
+  return a.scatter != nullptr ? 1 : (a.row_scale != nullptr || a.addend != nullptr) ? 2 : 0;
+}
+
+template <class CFG, bool ACT, bool OFF32, int DEC>
 static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
   // the dynamic-LDS limit is a per-device attribute of the kernel: raise it once per device
   static std::atomic<bool> attr_set[64];
@@ -550,7 +563,7 @@ static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
   }
   // a first GEMM (ACT) may carry the dense extra segment, a second one the output decode (DEC)
   if (ACT ? (a.scatter != nullptr || a.addend != nullptr) : a.xrows != 0) return SCMOE_ERR_ARG;
-  if (DEC != (a.scatter != nullptr) || (DEC && (a.addend == nullptr || a.row_scale == nullptr))) return SCMOE_ERR_ARG;
+  if (DEC != decode_kind(a) || (DEC == 1 && (a.addend == nullptr || a.row_scale == nullptr))) return SCMOE_ERR_ARG;
   // upper bound on row tiles: sum_e ceil(c_e / BM) <= max_rows / BM + E
   const int mtb = max_rows / CFG::BM + a.E + (a.xrows + CFG::BM - 1) / CFG::BM;
   a.nt = (a.N + CFG::BN - 1) / CFG::BN;
@@ -585,12 +598,18 @@ static int launch_gemm(const GemmArgs& a, int max_rows, int64_t a_rows, hipStrea
   const bool off32 = a_rows * a.lda * 2 < lim && static_cast<int64_t>(a.N) * a.ldw * 2 < lim &&
                      static_cast<int64_t>(a.xrows) * a.xlda * 2 < lim && static_cast<int64_t>(a.N) * a.xldw * 2 < lim;
   if constexpr (!ACT) {
-    if (a.scatter != nullptr)
-      return off32 ? launch_gemm_impl<CFG, ACT, true, true>(a, max_rows, stream)
-                   : launch_gemm_impl<CFG, ACT, false, true>(a, max_rows, stream);
+    switch (decode_kind(a)) {
+      case 1:
+        return off32 ? launch_gemm_impl<CFG, ACT, true, 1>(a, max_rows, stream)
+                     : launch_gemm_impl<CFG, ACT, false, 1>(a, max_rows, stream);
+      case 2:
+        return off32 ? launch_gemm_impl<CFG, ACT, true, 2>(a, max_rows, stream)
+                     : launch_gemm_impl<CFG, ACT, false, 2>(a, max_rows, stream);
+      default: break;
+    }
   }
-  return off32 ? launch_gemm_impl<CFG, ACT, true, false>(a, max_rows, stream)
-               : launch_gemm_impl<CFG, ACT, false, false>(a, max_rows, stream);
+  return off32 ? launch_gemm_impl<CFG, ACT, true, 0>(a, max_rows, stream)
+               : launch_gemm_impl<CFG, ACT, false, 0>(a, max_rows, stream);
 }
 
 template <bool ACT>
@@ -678,6 +697,7 @@ int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   if (a.max_rows <= 0) return SCMOE_OK;
   if (gemm_skinny_fits(a.max_rows, a.E)) {
     // a handful of rows per expert (a decode step): bound by streaming the weights, not by the matrix cores
+    if (a.scatter == nullptr && (a.row_scale != nullptr || a.addend != nullptr)) return SCMOE_ERR_ARG;
     const SplitK none;
     const int st1 = launch_gemm_skinny(first_gemm(a, none), true, a.max_rows, a.scratch, a.scratch_bytes, stream);
     if (st1 != SCMOE_OK) return st1;

@@ -50,7 +50,7 @@ static int check_desc(const scmoe_desc* D, int kmin, int kmax) {
 // Carves the layer workspace.  Every piece starts on a 256-byte boundary.
 struct LayerWs {
   int32_t* expert_idx; float* gate_w; int32_t* counts; int32_t* offsets; int32_t* dst_row;
-  int32_t* src_token; int32_t* offsets_shared; int32_t* offsets_c; float* coef; void* disp_ws; size_t disp_bytes;
+  int32_t* src_token; int32_t* offsets_shared; int32_t* offsets_c; float* coef; float* gate_cg; void* disp_ws; size_t disp_bytes;
   void* x_perm; void* hidden; void* y_perm; void* hidden_s; void* s;
   void* scratch_r; void* scratch_s; size_t scratch_bytes;   // GEMM scratch of the routed / shared chain
   int64_t ldh;   // row stride of hidden and hidden_s
@@ -78,6 +78,7 @@ static LayerWs carve(const scmoe_desc* D, void* base, bool shared) {
   w.offsets_shared = static_cast<int32_t*>(take(8));
   w.offsets_c = static_cast<int32_t*>(take(static_cast<size_t>(D->E + 1) * 4));   // offload: present experts only
   w.coef = static_cast<float*>(take(D->cg_mode ? static_cast<size_t>(D->T) * 8 : 0));
+  w.gate_cg = static_cast<float*>(take(D->cg_mode ? static_cast<size_t>(D->T) * 4 : 0));   // gate weight x routed coefficient
   w.disp_bytes = dispatch_ws_bytes(D->T, D->E, D->k);
   w.disp_ws = take(w.disp_bytes);
   w.x_perm = take(rows * D->d * eb);
@@ -93,6 +94,12 @@ static LayerWs carve(const scmoe_desc* D, void* base, bool shared) {
   }
   w.total = off;
   return w;
+}
+
+// out[t] = gate_w[t] * coef[2 t + 1]: the factor of a token's routed row under a coefficient gate (top-1)
+__global__ void scale_gate(const float* __restrict__ gate_w, const float* __restrict__ coef, float* __restrict__ out, int T) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < T) out[t] = gate_w[t] * coef[2 * static_cast<int64_t>(t) + 1];
 }
 
 __global__ void set_pair(int32_t* p, int a, int b) {
@@ -167,10 +174,12 @@ static int copy_routing(const scmoe_desc* D, const LayerWs& w, const scmoe_routi
 // the shared expert has written there; `before_ffn` (optional) is waited for first.
 // With shared != nullptr (MFMA path, same stream) the shared expert runs here too: its first
 // GEMM rides in the launch of the routed experts' first GEMM as one more segment.
+// With fused_y and row_coef != nullptr (coefficient gate, Eq. (14)-(17)) the decoded rows are
+// also scaled by the routed coefficient row_coef[2 t + 1] of their token.
 static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const scmoe_weights* W,
                         const LayerWs& w, hipStream_t stream, void* fused_y = nullptr, int64_t ld_fused = 0,
                         hipEvent_t before_ffn = nullptr, const FfnArgs* shared = nullptr,
-                        const ScanChores* chores = nullptr) {
+                        const ScanChores* chores = nullptr, const float* row_coef = nullptr) {
   SCMOE_TRY(gate_topk(x, ldx, D->dtype, W->W_g, W->bias, D->T, D->d, D->E, D->k, D->normalize,
                       w.expert_idx, w.gate_w, nullptr, stream));
   const bool gol = gather_on_load(D);
@@ -199,6 +208,11 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
     }
     a.y = fused_y; a.ldy = ld_fused;
     a.scatter = w.src_token; a.row_scale = w.gate_w; a.addend = fused_y; a.ldadd = ld_fused;
+    if (row_coef != nullptr) {
+      hipLaunchKernelGGL(scale_gate, dim3((D->T + 255) / 256), dim3(256), 0, stream, w.gate_w, row_coef, w.gate_cg, D->T);
+      SCMOE_TRY(launch_status());
+      a.row_scale = w.gate_cg;
+    }
   }
   if (shared != nullptr) {
     FfnArgs se = *shared;
@@ -352,11 +366,13 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
     hipLaunchKernelGGL(set_pair, dim3(1), dim3(64), 0, s_shared, w.offsets_shared, 0, D->T);
     SCMOE_TRY(launch_status());
   }
-  // Fused output decode: for top-1 routing without coefficient gate or residual, on the MFMA
-  // path, the shared expert writes y and the routed GEMM2 adds its gate-weighted rows into
-  // y[src_token[r]] (every row is written once, dropped tokens keep SE(x_cur)): no y_perm
-  // round trip and no combine kernel.  Needs y not to overlap the inputs, which are still
-  // being read when y is first written.
+  // Fused output decode: for top-1 routing on the MFMA path, the shared expert writes y and the
+  // routed GEMM2 adds its gate-weighted rows into y[src_token[r]] (every row is written once,
+  // dropped tokens keep SE(x_cur)): no y_perm round trip and no combine kernel.  Needs y not
+  // to overlap the inputs, which are still being read when y is first written.  With a
+  // coefficient gate or a residual the shared expert's GEMM2 decodes too (in place: its rows
+  // times the shared coefficient, plus the residual rows), and the routed rows carry the
+  // routed coefficient in their factor; the few-row kernels do not have that form.
   const size_t eb = elem_bytes(D->dtype);
   auto overlaps = [&](const void* a, int64_t lda_, const void* b, int64_t ldb_) {
     const unsigned char* a0 = static_cast<const unsigned char*>(a);
@@ -364,8 +380,12 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
     const size_t an = static_cast<size_t>(D->T) * lda_ * eb, bn = static_cast<size_t>(D->T) * ldb_ * eb;
     return a0 < b0 + bn && b0 < a0 + an;
   };
-  const bool fused = D->k == 1 && D->cg_mode == SCMOE_CG_NONE && !residual && gather_on_load(D) &&
-                     !overlaps(y, ldy, x_prev, ld_prev) && !overlaps(y, ldy, x_cur, ld_cur);
+  const bool extras = D->cg_mode != SCMOE_CG_NONE || residual != nullptr;
+  const bool tiled = !gemm_skinny_fits(D->T, 1) &&
+                     !gemm_skinny_fits(static_cast<int>(packed_rows(D->T, D->E, D->k, D->capacity)), D->E);
+  const bool fused = D->k == 1 && gather_on_load(D) && !overlaps(y, ldy, x_prev, ld_prev) &&
+                     !overlaps(y, ldy, x_cur, ld_cur) &&
+                     (!extras || (tiled && (!residual || !overlaps(y, ldy, residual, ldres))));
   FfnArgs se{};
   se.x = x_cur; se.ldx = ld_cur; se.gather = nullptr; se.offsets = w.offsets_shared;
   se.max_rows = D->T; se.E = 1; se.d = D->d; se.F = D->F;
@@ -375,9 +395,15 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   se.scratch = w.scratch_bytes ? w.scratch_s : nullptr; se.scratch_bytes = w.scratch_bytes;
   se.y = fused ? y : w.s;
   se.ldy = fused ? ldy : D->d;
-  if (!joint) SCMOE_TRY(expert_ffn_any(se, D->dtype, s_shared));
-  if (D->cg_mode != SCMOE_CG_NONE)
+  const float* coef = D->cg_mode != SCMOE_CG_NONE ? w.coef : nullptr;
+  if (fused && extras) {
+    se.row_scale = coef;
+    se.addend = residual;
+    se.ldadd = ldres;
+  }
+  if (coef != nullptr)
     SCMOE_TRY(coef_gate(x_cur, ld_cur, D->dtype, W->W_cg, D->cg_mode, D->T, D->d, w.coef, s_shared));
+  if (!joint) SCMOE_TRY(expert_ffn_any(se, D->dtype, s_shared));
   if (two) {
     hipError_t e = hipEventRecord(ev->join, sa);
     if (e != hipSuccess) return hip_fail(e);
@@ -385,7 +411,7 @@ extern "C" int scmoe_layer_forward(const scmoe_desc* D, const void* x_prev, int6
   // routed experts on the preceding-layer representation
   if (fused) {
     SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, y, ldy, two ? ev->join : nullptr, joint ? &se : nullptr,
-                           joint ? &chores : nullptr));
+                           joint ? &chores : nullptr, coef));
     return copy_routing(D, w, routing, sm);
   }
   SCMOE_TRY(routed_chain(D, x_prev, ld_prev, W, w, sm, nullptr, 0, nullptr, joint ? &se : nullptr,
