@@ -139,43 +139,55 @@ int combine(const void* y_perm, int64_t ldyp, int dtype, const int32_t* dst_row,
   return launch_status();
 }
 
-// Coefficient gate: one wave per token, fp32 dot products reduced across the wave.
-template <bool BF16>
+// Coefficient gate: one wave per token at a time, fp32 dot products reduced across the wave.
+// LDS_W: the gate's one or two weight rows are staged in LDS once per workgroup, which then
+// walks over many tokens (read from global memory per token they cost two to four times
+// the bytes of the token's row in cache traffic); otherwise they are read in place (rows too
+// long for the LDS).
+template <bool BF16, bool LDS_W>
 __global__ __launch_bounds__(256) void coef_gate_kernel(const unsigned char* __restrict__ x, int64_t ldx_bytes,
                                                         const float* __restrict__ Wcg, int mode, int T,
                                                         int d, float* __restrict__ coef) {
   constexpr int NV = BF16 ? 8 : 4;
+  extern __shared__ __attribute__((aligned(16))) float cg_w[];
+  if (LDS_W) {
+    const int n = (mode == SCMOE_CG_2 ? 2 : 1) * d;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) cg_w[i] = Wcg[i];
+    __syncthreads();
+  }
+  auto w = [&](int i) { return LDS_W ? cg_w[i] : Wcg[i]; };
   const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (t >= T) return;
-  const unsigned char* row = x + static_cast<int64_t>(t) * ldx_bytes;
-  float a = 0.0f, b = 0.0f;
-  for (int i0 = lane * NV; i0 < d; i0 += 64 * NV) {
-    float v[8];
-    load8<BF16>(row + static_cast<int64_t>(i0) * (BF16 ? 2 : 4), v);
+  const int waves = blockDim.x >> 6;
+  for (int t = blockIdx.x * waves + (threadIdx.x >> 6); t < T; t += gridDim.x * waves) {
+    const unsigned char* row = x + static_cast<int64_t>(t) * ldx_bytes;
+    float a = 0.0f, b = 0.0f;
+    for (int i0 = lane * NV; i0 < d; i0 += 64 * NV) {
+      float v[8];
+      load8<BF16>(row + static_cast<int64_t>(i0) * (BF16 ? 2 : 4), v);
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      a = fmaf(v[i], Wcg[i0 + i], a);
-      if (mode == SCMOE_CG_2) b = fmaf(v[i], Wcg[d + i0 + i], b);
+      for (int i = 0; i < NV; ++i) {
+        a = fmaf(v[i], w(i0 + i), a);
+        if (mode == SCMOE_CG_2) b = fmaf(v[i], w(d + i0 + i), b);
+      }
     }
-  }
-  for (int off = 32; off > 0; off >>= 1) {
-    a += __shfl_xor(a, off, 64);
-    b += __shfl_xor(b, off, 64);
-  }
-  if (lane == 0) {
-    float c0, c1;
-    if (mode == SCMOE_CG_1) {
-      c0 = 1.0f / (1.0f + expf(-a));
-      c1 = 1.0f;
-    } else {
-      const float m = fmaxf(a, b);
-      const float ea = expf(a - m), eb = expf(b - m);
-      c0 = ea / (ea + eb);
-      c1 = eb / (ea + eb);
+    for (int off = 32; off > 0; off >>= 1) {
+      a += __shfl_xor(a, off, 64);
+      b += __shfl_xor(b, off, 64);
     }
-    coef[2 * static_cast<int64_t>(t)] = c0;
-    coef[2 * static_cast<int64_t>(t) + 1] = c1;
+    if (lane == 0) {
+      float c0, c1;
+      if (mode == SCMOE_CG_1) {
+        c0 = 1.0f / (1.0f + expf(-a));
+        c1 = 1.0f;
+      } else {
+        const float m = fmaxf(a, b);
+        const float ea = expf(a - m), eb = expf(b - m);
+        c0 = ea / (ea + eb);
+        c1 = eb / (ea + eb);
+      }
+      coef[2 * static_cast<int64_t>(t)] = c0;
+      coef[2 * static_cast<int64_t>(t) + 1] = c1;
+    }
   }
 }
 
@@ -187,12 +199,24 @@ int coef_gate(const void* x, int64_t ldx, int dtype, const float* Wcg, int mode,
   if (T == 0) return SCMOE_OK;
   if (!x || !Wcg || !coef) return SCMOE_ERR_NULL;
   if (!view_ok(x, ldx, d, dtype)) return SCMOE_ERR_SHAPE;
-  dim3 grid((T + 3) / 4), block(256);
   const unsigned char* xb = static_cast<const unsigned char*>(x);
-  if (dtype == SCMOE_BF16)
-    hipLaunchKernelGGL((coef_gate_kernel<true>), grid, block, 0, stream, xb, ldx * 2, Wcg, mode, T, d, coef);
-  else
-    hipLaunchKernelGGL((coef_gate_kernel<false>), grid, block, 0, stream, xb, ldx * 4, Wcg, mode, T, d, coef);
+  const size_t lds = static_cast<size_t>(mode == SCMOE_CG_2 ? 2 : 1) * d * sizeof(float);
+  const int wgs = (T + 3) / 4;
+  if (lds <= 48 * 1024) {
+    // weight rows in LDS: a few workgroups per CU, each over many tokens
+    const int cap = 8 * num_cus();
+    dim3 grid(wgs < cap ? wgs : cap), block(256);
+    if (dtype == SCMOE_BF16)
+      hipLaunchKernelGGL((coef_gate_kernel<true, true>), grid, block, lds, stream, xb, ldx * 2, Wcg, mode, T, d, coef);
+    else
+      hipLaunchKernelGGL((coef_gate_kernel<false, true>), grid, block, lds, stream, xb, ldx * 4, Wcg, mode, T, d, coef);
+  } else {
+    dim3 grid(wgs), block(256);
+    if (dtype == SCMOE_BF16)
+      hipLaunchKernelGGL((coef_gate_kernel<true, false>), grid, block, 0, stream, xb, ldx * 2, Wcg, mode, T, d, coef);
+    else
+      hipLaunchKernelGGL((coef_gate_kernel<false, false>), grid, block, 0, stream, xb, ldx * 4, Wcg, mode, T, d, coef);
+  }
   return launch_status();
 }
 
