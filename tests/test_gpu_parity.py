@@ -404,6 +404,27 @@ def test_layer_in_place_output(oracle):
     assert relerr(to_host(y2), to_host(y)) <= 1e-2
 
 
+@pytest.mark.parametrize("cg", [0, 1, 2])
+def test_layer_output_in_place_of_the_residual(oracle, cg):
+    """y may be the residual's buffer (y = layer(x) + y): the fused decode of the residual and
+    coefficient-gate forms is skipped then; with a buffer of its own it runs, same result."""
+    L = inputs.make_layer(T=900, d=128, F=256, E=4, dtype="bf16", seed=62 + cg, biases=True, cg_rows=cg, w_scale=0.05)
+    D = DevLayer(L, "bf16")
+    ref, rr = oracle.layer_forward(L["x_prev"], L["x_cur"], L, k=1, capacity_=300, shared=1, cg_mode=cg,
+                                   add_residual=1)
+    desc = B.make_desc(D.T, D.d, D.F, D.E, 1, 300, D.code, 0, 0, cg)
+    ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
+    y = D.x_cur.clone()
+    B.scmoe_layer_forward(desc, D.x_prev, D.x_cur, D.weights, y, ws, residual=y)
+    torch.cuda.synchronize()
+    assert relerr(to_host(y), ref) <= TOL["bf16"]
+    y2 = torch.empty_like(y)
+    B.scmoe_layer_forward(desc, D.x_prev, D.x_cur, D.weights, y2, ws, residual=D.x_cur.clone())
+    torch.cuda.synchronize()
+    assert relerr(to_host(y2), ref) <= TOL["bf16"]
+    assert relerr(to_host(y2), to_host(y)) <= 1e-2
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_layer_random_configurations(oracle, seed):
     """Seeded sweep over shapes and options: widths on and off the MFMA path (multiples of 64
