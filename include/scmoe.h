@@ -298,7 +298,9 @@ int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out);
  * desc->k = 1 is ScMoE; desc->k = 2 routes two experts per token on x_prev (ScMoE-2,
  * appendix "more activated experts"); larger k up to SCMOE_MAX_TOPK follows the same rule.
  * With desc->cg_mode != 0 the coefficient gate reads x_cur.
- * residual may be NULL.  routing may be NULL.  No host synchronisation happens inside, no
+ * residual may be NULL.  routing may be NULL.  y may be the buffer of x_prev, x_cur or
+ * residual (same pointer and row stride; any other overlap is not supported): the call then
+ * takes a path that has read a row before it writes it.  No host synchronisation happens inside, no
  * memory is allocated and no memset is enqueued, so the call can be captured in a HIP graph
  * (after one ordinary call on the device, which creates the events and sets kernel attributes).
  * Reproducibility: the routing is the same in every mode; y is the same bits for the same
