@@ -204,6 +204,18 @@ def test_expert_ffn_padded_row_strides(oracle, E, lens, d, F, dtype):
     assert np.array_equal(g, g0)
 
 
+@pytest.mark.parametrize("E,lens,d,F", [
+    (3, [2100, 0, 1900], 128, 4096),      # first GEMM: 17 row tiles x 16 column tiles
+    (3, [1900, 2100, 0], 4096, 128),      # second GEMM: the same
+    (6, [300, 700, 1, 1500, 256, 1300], 128, 4096)])
+@pytest.mark.parametrize("workspace", [False, True])
+def test_expert_ffn_many_tiles(oracle, E, lens, d, F, workspace):
+    """More than 256 tiles of 256 x 256 in one GEMM, every element compared: the schedule
+    then deals chunks of 32 tiles to the 8 XCDs in turn and cuts only the rest into eighths;
+    raster groups of several sizes per expert; with a workspace the last round is cut along K."""
+    _ffn_case(oracle, E, lens, d, F, "bf16", True, 0, extra_rows=3, workspace=workspace)
+
+
 @pytest.mark.parametrize("E,lens,d,F,biases,gelu_mode,pad", [
     (4, [3, 0, 7, 1], 128, 256, True, 0, False),
     (1, [32], 64, 64, False, 0, False),
