@@ -81,7 +81,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 
   // ---- tile schedule ------------------------------------------------------------------------
   const int nk_all = p.Kd / BK;
-  const TileSchedule<BM, BN, ACT ? CFG::GM_FIRST : CFG::GM_SECOND> sched(p, nk_all, p.splitk_part != nullptr);
+  TileSchedule<BM, BN, ACT ? CFG::GM_FIRST : CFG::GM_SECOND> sched(p, nk_all, p.splitk_part != nullptr);
   const int nslots = sched.nslots;
   int it = blockIdx.x >> 3;                // work item: a tile, or one K-part of a tile of the last round
   if (it >= sched.nitems) return;

@@ -178,6 +178,7 @@ struct TileSchedule {
   // (nearly) all workgroups busy.  Item it < full is local tile it; item full + w is part
   // w % S of local tile full + w / S.  A workgroup takes items slot, slot + nslots, ...
   int full, rem, S, nitems, xcd;
+  int cur_e = 0, cur_base = 0;    // where the last search through offsets[] ended (see locate)
 
   __device__ __forceinline__ TileSchedule(const GemmArgs& p, int nk, bool can_split)
       : mt_seg(0), nt(p.nt), E(p.E), xt((p.xrows + BM - 1) / BM), xrows(p.xrows), offsets(p.offsets) {
@@ -242,7 +243,11 @@ struct TileSchedule {
   }
   // local tile l -> expert e (E: the dense extra segment), packed rows [row0, row_end)
   // (row0 + BM may exceed row_end), column n0
-  __device__ __forceinline__ void locate(int l, int& e, int& row0, int& row_end, int& n0) const {
+  // The tiles of a workgroup come in ascending order, so the search through offsets[] goes on
+  // from the expert of the previous tile (cur_e, with cur_base tiles in the experts before
+  // it) instead of from expert 0: a dependent scalar load per expert passed, 2 us per tile
+  // at 16 experts when started from 0 every time.
+  __device__ __forceinline__ void locate(int l, int& e, int& row0, int& row_end, int& n0) {
     int mt;
     if (l < na) {
       raster(a0 + l, xt, mt, n0);
@@ -258,17 +263,24 @@ struct TileSchedule {
     row0 = 0;
     row_end = 1;
     n0 = 0;
-    for (e = 0; e < E; ++e) {
+    if (t < cur_base) {        // not expected; start over
+      cur_e = 0;
+      cur_base = 0;
+    }
+    int base = cur_base;
+    for (e = cur_e; e < E; ++e) {
       const int s = offsets[e];
       const int c = offsets[e + 1] - s;
       const int ntile = (c + BM - 1) / BM;
-      if (t < ntile * nt) {
-        raster(t, ntile, mt, n0);
+      if (t - base < ntile * nt) {
+        raster(t - base, ntile, mt, n0);
         row0 = s + mt * BM;
         row_end = s + c;
+        cur_e = e;
+        cur_base = base;
         break;
       }
-      t -= ntile * nt;
+      base += ntile * nt;
     }
     if (e == E) e = E - 1;   // not reachable for a tile of this XCD's share
   }
