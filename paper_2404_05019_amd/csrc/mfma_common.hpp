@@ -46,6 +46,7 @@ struct GemmArgs {
   int E, N, Kd;
   int nt;                   // column tiles
   int gelu_mode;
+  int stream_out;           // store C with the streaming (non-temporal) hint
   // Fused output decode (optional; scatter == nullptr stores C[r, :] as is).  Packed row r
   // is written to row t = scatter[r] of C as  addend[t, :] + row_scale[t] * (sum + bias).
   const int32_t* scatter;
