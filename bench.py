@@ -21,7 +21,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # Memory traffic of one grouped-GEMM launch (bytes), from two rocprofv3 --pmc passes
 # (FETCH_SIZE, WRITE_SIZE) scaled by a 1 GiB copy in the same run: see
 # profiles/gemm_bf16_kernel_large_pmc.txt.  Only measured for the workload it is keyed by.
-GEMM_TRAFFIC_BYTES = {"large": 2.5e9}
+GEMM_TRAFFIC_BYTES = {"large": 2.4e9}
 
 
 def parse():
