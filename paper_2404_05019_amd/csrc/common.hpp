@@ -90,7 +90,7 @@ struct FfnArgs {
   void* y; int64_t ldy;            // [rows, d]
   int gelu_mode;
   // Fused output decode of the second GEMM (MFMA path only; all three pointers nullptr: off).
-  // With scatter:
+  // With scatter (addend optional in the tiled kernel, required by the few-row one):
   //   y[scatter[r], :] = addend[scatter[r], :] + row_scale[scatter[r]] * (W2 . hidden[r] + b2)
   // Without scatter (rows stay in place; tiled kernel only, not the few-row one), row_scale
   // holding PAIRS of coefficients per row of which the first is used, either pointer optional:

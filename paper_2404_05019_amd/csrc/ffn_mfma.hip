@@ -60,7 +60,8 @@ struct TileCfg {
 };
 
 // DEC: output decode in the epilogue of a second GEMM.  0: none.  1: row r of the packed
-// output goes to token scatter[r]: C[scatter[r]] = addend[scatter[r]] + row_scale[scatter[r]] * row.
+// output goes to token scatter[r]: C[scatter[r]] = addend[scatter[r]] + row_scale[scatter[r]] * row
+// (addend may be null: nothing is added).
 // 2: rows stay where they are: C[r] = addend[r] + row_scale[2 r] * row (row_scale: pairs of
 // coefficients per row, the first one is used; either pointer may be null).
 template <class CFG, bool ACT, bool OFF32, int DEC>
@@ -360,7 +361,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       for (int g = 0; g < PIECES; ++g) {
         const int tok = __shfl(dtok[i >> 1], (i & 1) * 32 + g * 8 + (lane >> 3));
         dadd[g] = make_uint4(0u, 0u, 0u, 0u);
-        if (n < p.N && (DEC == 1 || p.addend != nullptr))
+        if (n < p.N && p.addend != nullptr)
           dadd[g] = *reinterpret_cast<const uint4*>(p.addend + (static_cast<int64_t>(tok) * p.ldadd + n) * 2);
       }
     };
@@ -571,7 +572,7 @@ static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
   }
   // a first GEMM (ACT) may carry the dense extra segment, a second one the output decode (DEC)
   if (ACT ? (a.scatter != nullptr || a.addend != nullptr) : a.xrows != 0) return SCMOE_ERR_ARG;
-  if (DEC != decode_kind(a) || (DEC == 1 && (a.addend == nullptr || a.row_scale == nullptr))) return SCMOE_ERR_ARG;
+  if (DEC != decode_kind(a) || (DEC == 1 && a.row_scale == nullptr)) return SCMOE_ERR_ARG;
   // upper bound on row tiles: sum_e ceil(c_e / BM) <= max_rows / BM + E
   const int mtb = max_rows / CFG::BM + a.E + (a.xrows + CFG::BM - 1) / CFG::BM;
   a.nt = (a.N + CFG::BN - 1) / CFG::BN;

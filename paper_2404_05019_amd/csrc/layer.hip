@@ -102,6 +102,17 @@ __global__ void scale_gate(const float* __restrict__ gate_w, const float* __rest
   if (t < T) out[t] = gate_w[t] * coef[2 * static_cast<int64_t>(t) + 1];
 }
 
+// One wave per token: the output row of a token whose (single) routed item was dropped is
+// set to zero (standard top-1 layer with the decode fused into the second GEMM, which only
+// writes the rows of kept tokens).  pieces = 16-byte pieces per row.
+__global__ __launch_bounds__(256) void zero_dropped_rows(unsigned char* __restrict__ y, int64_t ldy_bytes,
+                                                         const int32_t* __restrict__ dst_row, int T, int pieces) {
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T || dst_row[t] >= 0) return;
+  for (int c = threadIdx.x & 63; c < pieces; c += 64)
+    *reinterpret_cast<uint4*>(y + static_cast<int64_t>(t) * ldy_bytes + static_cast<int64_t>(c) * 16) = make_uint4(0u, 0u, 0u, 0u);
+}
+
 __global__ void set_pair(int32_t* p, int a, int b) {
   if (threadIdx.x == 0) {
     p[0] = a;
@@ -176,10 +187,13 @@ static int copy_routing(const scmoe_desc* D, const LayerWs& w, const scmoe_routi
 // GEMM rides in the launch of the routed experts' first GEMM as one more segment.
 // With fused_y and row_coef != nullptr (coefficient gate, Eq. (14)-(17)) the decoded rows are
 // also scaled by the routed coefficient row_coef[2 t + 1] of their token.
+// With fused_y and nothing_below (standard top-1 layer: no shared expert has written fused_y)
+// the decoded rows are stored as they are and the rows of dropped tokens are set to zero.
 static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const scmoe_weights* W,
                         const LayerWs& w, hipStream_t stream, void* fused_y = nullptr, int64_t ld_fused = 0,
                         hipEvent_t before_ffn = nullptr, const FfnArgs* shared = nullptr,
-                        const ScanChores* chores = nullptr, const float* row_coef = nullptr) {
+                        const ScanChores* chores = nullptr, const float* row_coef = nullptr,
+                        bool nothing_below = false) {
   SCMOE_TRY(gate_topk(x, ldx, D->dtype, W->W_g, W->bias, D->T, D->d, D->E, D->k, D->normalize,
                       w.expert_idx, w.gate_w, nullptr, stream));
   const bool gol = gather_on_load(D);
@@ -208,6 +222,13 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
     }
     a.y = fused_y; a.ldy = ld_fused;
     a.scatter = w.src_token; a.row_scale = w.gate_w; a.addend = fused_y; a.ldadd = ld_fused;
+    if (nothing_below) {
+      a.addend = nullptr;
+      hipLaunchKernelGGL(zero_dropped_rows, dim3((D->T + 3) / 4), dim3(256), 0, stream, static_cast<unsigned char*>(fused_y),
+                         ld_fused * static_cast<int64_t>(elem_bytes(D->dtype)), w.dst_row, D->T,
+                         static_cast<int>(D->d * elem_bytes(D->dtype) / 16));
+      SCMOE_TRY(launch_status());
+    }
     if (row_coef != nullptr) {
       hipLaunchKernelGGL(scale_gate, dim3((D->T + 255) / 256), dim3(256), 0, stream, w.gate_w, row_coef, w.gate_cg, D->T);
       SCMOE_TRY(launch_status());
@@ -601,6 +622,19 @@ extern "C" int moe_topk_layer_forward(const scmoe_desc* D, const void* x, int64_
   const LayerWs w = carve(D, workspace, false);
   if (ws_bytes < w.total) return SCMOE_ERR_WORKSPACE;
   hipStream_t sm = static_cast<hipStream_t>(stream);
+  // Top-1 on the tiled MFMA path with y apart from x: the second GEMM decodes in its epilogue
+  // (y[src_token[r]] = gate weight x row; dropped tokens' rows are zeroed by a kernel of their
+  // own), no y_perm round trip and no combine launch.
+  const unsigned char* x0 = static_cast<const unsigned char*>(x);
+  const unsigned char* y0 = static_cast<const unsigned char*>(y);
+  const size_t eb = elem_bytes(D->dtype);
+  const bool apart = x0 + static_cast<size_t>(D->T) * ldx * eb <= y0 || y0 + static_cast<size_t>(D->T) * ldy * eb <= x0;
+  const bool fused = D->k == 1 && gather_on_load(D) && apart &&
+                     !gemm_skinny_fits(static_cast<int>(packed_rows(D->T, D->E, D->k, D->capacity)), D->E);
+  if (fused) {
+    SCMOE_TRY(routed_chain(D, x, ldx, W, w, sm, y, ldy, nullptr, nullptr, nullptr, nullptr, true));
+    return copy_routing(D, w, routing, sm);
+  }
   SCMOE_TRY(routed_chain(D, x, ldx, W, w, sm));
   SCMOE_TRY(combine(w.y_perm, D->d, D->dtype, w.dst_row, w.gate_w, D->T, D->d, D->k, nullptr, 0, nullptr, 0,
                     nullptr, y, ldy, sm));

@@ -73,7 +73,7 @@ def run_layer(D, k=1, capacity=None, shared=True, normalize=0, cg_mode=0, gelu_m
     C_ = T * k if capacity is None else capacity
     desc = B.make_desc(T, D.d, D.F, E, k, C_, D.code, gelu_mode, normalize, cg_mode)
     ws = torch.empty(B.scmoe_workspace_bytes(desc), dtype=torch.uint8, device=DEV)
-    y = torch.empty((T, D.d), dtype=D.tdtype, device=DEV)
+    y = torch.full((T, D.d), float("nan"), dtype=D.tdtype, device=DEV)   # a row left unwritten fails the comparison
     rows = min(T * k, E * C_)
     r = dict(expert_idx=torch.empty(T * k, dtype=torch.int32, device=DEV),
              gate_w=torch.empty(T * k, dtype=torch.float32, device=DEV),
