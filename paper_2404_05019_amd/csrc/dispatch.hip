@@ -128,6 +128,115 @@ __global__ __launch_bounds__(DISP_BLOCK) void dispatch_rank(
   }
 }
 
+// hist + scan + rank in ONE workgroup of 16 waves for calls of at most DISP_SMALL_ITEMS items
+// (decode steps), where three dependent launches cost more than the work: the items are
+// walked in chunks of 1024 (a lane keeps the experts of its items in registers), once to
+// count and once to rank; same results as the three kernels.  (Measured: 5 us less per layer
+// call up to 1024 tokens, even at 2048; with 8 or 16 chunks one workgroup takes 10-17 us
+// longer than the three kernels.)
+constexpr int DISP_SMALL_THREADS = 1024;
+constexpr int DISP_SMALL_CHUNKS = 2;
+constexpr int DISP_SMALL_ITEMS = DISP_SMALL_THREADS * DISP_SMALL_CHUNKS;
+
+__global__ __launch_bounds__(DISP_SMALL_THREADS) void dispatch_small(
+    const int32_t* __restrict__ expert_idx, int T, int k, int E, int capacity, int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets, int32_t* __restrict__ dst_row, int32_t* __restrict__ src_token,
+    const ScanChores ch) {
+  constexpr int NW = DISP_SMALL_THREADS / 64;
+  __shared__ int wcnt[NW][SCMOE_MAX_EXPERTS];     // items per (wave, expert) of the current chunk
+  __shared__ int seen[SCMOE_MAX_EXPERTS];         // items per expert: all (first pass) / in earlier chunks (second)
+  __shared__ int offs[SCMOE_MAX_EXPERTS + 1];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  if (ch.pair != nullptr && tid == 0) {
+    ch.pair[0] = 0;
+    ch.pair[1] = ch.pair_hi;
+  }
+  for (int i = tid; i < ch.nzero; i += DISP_SMALL_THREADS) {
+    if (ch.zero_a != nullptr) ch.zero_a[i] = 0;
+    if (ch.zero_b != nullptr) ch.zero_b[i] = 0;
+  }
+  const int n = T * k;
+  const int nchunk = (n + DISP_SMALL_THREADS - 1) / DISP_SMALL_THREADS;
+  if (tid < SCMOE_MAX_EXPERTS) seen[tid] = 0;
+  __syncthreads();
+  // lanes of this wave that hold the same expert as this lane, and how many of them come before it
+  auto match = [&](int e, bool valid, int& before, int& total) {
+    unsigned long long same = __ballot(valid);
+    for (int b = 0; (1 << b) < E; ++b) {
+      const unsigned long long bal = __ballot(valid && ((e >> b) & 1));
+      same &= ((e >> b) & 1) ? bal : ~bal;
+    }
+    const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    before = __popcll(same & below);
+    total = __popcll(same);
+  };
+  int ev[DISP_SMALL_CHUNKS];
+#pragma unroll
+  for (int q = 0; q < DISP_SMALL_CHUNKS; ++q) {
+    ev[q] = -1;
+    if (q < nchunk) {
+      int t, j;
+      ev[q] = item_expert(expert_idx, q * DISP_SMALL_THREADS + tid, n, T, k, E, &t, &j);
+      int before, total;
+      match(ev[q], ev[q] >= 0, before, total);
+      if (ev[q] >= 0 && before == 0) atomicAdd(&seen[ev[q]], total);   // integer counts: order does not matter
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int e = 0; e < E; ++e) {
+      const int c = seen[e] < capacity ? seen[e] : capacity;
+      counts[e] = c;
+      offsets[e] = run;
+      offs[e] = run;
+      run += c;
+    }
+    offsets[E] = run;
+    offs[E] = run;
+  }
+  __syncthreads();
+  if (tid < SCMOE_MAX_EXPERTS) seen[tid] = 0;
+#pragma unroll
+  for (int q = 0; q < DISP_SMALL_CHUNKS; ++q) {
+    if (q < nchunk) {
+      for (int c = tid; c < NW * SCMOE_MAX_EXPERTS; c += DISP_SMALL_THREADS) (&wcnt[0][0])[c] = 0;
+      __syncthreads();
+      const int e = ev[q];
+      const bool valid = e >= 0;
+      int before, total;
+      match(e, valid, before, total);
+      if (valid && before == 0) wcnt[wave][e] = total;
+      __syncthreads();
+      const int i = q * DISP_SMALL_THREADS + tid;
+      if (i < n) {
+        const int j = i / T;
+        const int t = i - j * T;
+        int out = -1;
+        if (valid) {
+          int slot = seen[e] + before;
+          for (int w = 0; w < wave; ++w) slot += wcnt[w][e];
+          if (slot < capacity) {
+            out = offs[e] + slot;
+            src_token[out] = t;
+          }
+        }
+        dst_row[static_cast<int64_t>(t) * k + j] = out;
+      }
+      __syncthreads();
+      if (tid < E) {
+        int add = 0;
+        for (int w = 0; w < NW; ++w) add += wcnt[w][tid];
+        seen[tid] += add;
+      }
+      // (the next chunk's clearing of wcnt comes after a barrier of its own: see below)
+      __syncthreads();
+    }
+  }
+}
+
 // x_perm[r, :] = x[src_token[r], :], 16 bytes per lane, one wave per row.
 __global__ __launch_bounds__(256) void gather_rows(const unsigned char* __restrict__ x, int64_t ldx_bytes,
                                                    const int32_t* __restrict__ src_token,
@@ -183,15 +292,20 @@ int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, i
   if (ws_bytes < dispatch_ws_bytes(T, E, k)) return SCMOE_ERR_WORKSPACE;
   if (T > 0 && !workspace) return SCMOE_ERR_NULL;
   const int nblk = disp_nblk(T, k);
-  int32_t* blockhist = static_cast<int32_t*>(workspace);
-  int32_t* blockbase = blockhist + static_cast<size_t>(nblk) * E;
-  if (nblk > 0)
+  const bool small = static_cast<int64_t>(T) * k <= DISP_SMALL_ITEMS;
+  if (small) {
+    hipLaunchKernelGGL(dispatch_small, dim3(1), dim3(DISP_SMALL_THREADS), 0, stream, expert_idx, T, k, E, capacity,
+                       counts, offsets, dst_row, src_token, chores ? *chores : ScanChores{});
+  } else {
+    int32_t* blockhist = static_cast<int32_t*>(workspace);
+    int32_t* blockbase = blockhist + static_cast<size_t>(nblk) * E;
     hipLaunchKernelGGL(dispatch_hist, dim3(nblk), dim3(DISP_BLOCK), 0, stream, expert_idx, T, k, E, blockhist);
-  hipLaunchKernelGGL(dispatch_scan, dim3(1), dim3(256), 0, stream, blockhist, nblk, E, capacity, blockbase,
-                     counts, offsets, chores ? *chores : ScanChores{});
-  if (nblk > 0) {
+    hipLaunchKernelGGL(dispatch_scan, dim3(1), dim3(256), 0, stream, blockhist, nblk, E, capacity, blockbase,
+                       counts, offsets, chores ? *chores : ScanChores{});
     hipLaunchKernelGGL(dispatch_rank, dim3(nblk), dim3(DISP_BLOCK), 0, stream, expert_idx, T, k, E, capacity,
                        blockbase, offsets, dst_row, src_token);
+  }
+  if (nblk > 0) {
     if (x_perm != nullptr) {
       const int64_t max_rows = static_cast<int64_t>(T) * k;
       int blocks = static_cast<int>((max_rows + 3) / 4);

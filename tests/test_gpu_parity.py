@@ -107,7 +107,9 @@ def _run_dispatch(x, idx, E, k, C_, dtype, copy=True):
     (1, 1, 1, 1, 8, "f32"), (63, 4, 1, 10, 16, "bf16"), (64, 4, 1, 0, 8, "f32"), (257, 4, 1, 257, 24, "bf16"),
     (5000, 8, 1, 700, 64, "bf16"), (5000, 16, 2, 500, 40, "f32"), (1025, 64, 2, 40, 8, "bf16"),
     (4096, 7, 2, 100000, 8, "f32"), (300, 1, 1, 17, 8, "bf16"), (3000, 8, 3, 900, 16, "bf16"),
-    (1000, 6, 4, 500, 8, "f32"), (257, 3, 3, 300, 8, "f32")])
+    (1000, 6, 4, 500, 8, "f32"), (257, 3, 3, 300, 8, "f32"),
+    # one-workgroup form (at most 2048 items): one chunk, the chunk boundary, both chunks full, one item past it
+    (1024, 8, 1, 100, 8, "f32"), (1025, 5, 1, 300, 8, "f32"), (1024, 16, 2, 90, 8, "bf16"), (683, 9, 3, 200, 8, "f32")])
 def test_dispatch_parity(oracle, T, E, k, C_, d, dtype):
     rng = np.random.default_rng(T * 7 + E)
     x = inputs.quantize(rng.standard_normal((T, d)), dtype)
