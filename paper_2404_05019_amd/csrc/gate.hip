@@ -261,12 +261,14 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
 // 64 tokens' worth of LDS traffic.  Here a lane owns one (token,
 // expert) chain: EPAD = E rounded up to a power of two lanes per token, 256 / EPAD tokens per
 // workgroup.  W_g and the tokens' rows are staged through LDS in chunks of `kch` features
-// with fully coalesced, independent loads (one memory latency per chunk); W_g is transposed
-// on the way in, so a chain reads 4 consecutive features of its expert (and 8 of its token)
-// with one 16-byte LDS read and the reads of many features are in flight at once.  Same
-// chain, same bits.
-// Dynamic LDS: W chunk [E][kch + 4] fp32, then the x chunk [256 / EPAD][kch] with 16 bytes of
-// row padding (both paddings spread the rows over the banks).
+// with fully coalesced, independent loads (one memory latency per chunk, and the next chunk's
+// are in flight meanwhile); W_g is transposed and x widened to fp32 on the way in, so a chain
+// reads 4 consecutive features of its expert and of its token with one 16-byte LDS read each,
+// 32 features ahead of the FMAs.  Same chain, same bits.
+// Dynamic LDS: W chunk [E][kch + 4] fp32, then the x chunk [256 / EPAD][kch] fp32 with 16
+// bytes of row padding (both paddings spread the rows over the banks).
+constexpr int GATE_SMALL_WREGS = 32;   // W_g values a thread holds of a chunk: ceil(kch / tokens per workgroup)
+constexpr int GATE_SMALL_XREGS = 8;    // 16-byte pieces of x a thread holds of a chunk
 template <bool BF16>
 __global__ __launch_bounds__(256) void gate_small_kernel(
     const unsigned char* __restrict__ x, int64_t ldx, const float* __restrict__ Wg,
@@ -285,53 +287,112 @@ __global__ __launch_bounds__(256) void gate_small_kernel(
   const int ec = e < E ? e : E - 1;
   float* wsm = reinterpret_cast<float*>(gsm);
   const int wrs = kch + 4;                         // float stride of a staged (transposed) W_g row
-  const int xrs = kch * EB + 16;                   // byte stride of a staged x row
+  const int xrs = kch * 4 + 16;                    // byte stride of a staged x row (widened to fp32)
   unsigned char* xsm = gsm + static_cast<size_t>(wrs) * E * 4;
   float acc = 0.0f;
-  for (int c0 = 0; c0 < d; c0 += kch) {
-    const int kn = (d - c0 < kch) ? d - c0 : kch;  // multiple of 8
-    __syncthreads();                               // the previous chunk has been consumed
-    // W_g rows c0 .. c0 + kn - 1, transposed: thread (tl, e) copies column e of rows tl, tl + tpw, ...
-    // (consecutive e: coalesced reads; epad is a power of two, so no division by E is needed)
-    if (e < E) {
-      const float* wsrc = Wg + static_cast<int64_t>(c0) * E + e;
-      float* wdst = wsm + e * wrs;
-#pragma unroll 8
-      for (int f = tl; f < kn; f += tpw) wdst[f] = wsrc[static_cast<int64_t>(f) * E];
+  // A chunk travels global memory -> registers -> LDS, and the next chunk's loads are in flight
+  // while this one is consumed (with few workgroups nothing else hides their latency; loaded
+  // and staged in one step, a call of 8 tokens spent 25 of its 40 us waiting for them).
+  // Thread (tl, e) holds column e of W_g rows tl, tl + tpw, ... of the chunk (consecutive e:
+  // coalesced reads; epad is a power of two, so no division by E is needed) and the 16-byte
+  // pieces tid, tid + 256, ... of the x rows.  All loads are unconditional on clamped indices.
+  constexpr int WMAX = GATE_SMALL_WREGS, XMAX = GATE_SMALL_XREGS;
+  float wpre[WMAX];
+  uint4 xpre[XMAX];
+  auto fetch = [&](int c0) {
+    const int kn = (d - c0 < kch) ? d - c0 : kch;
+    const float* wsrc = Wg + static_cast<int64_t>(c0) * E + ec;
+#pragma unroll
+    for (int u = 0; u < WMAX; ++u) {
+      int f = tl + u * tpw;
+      if (f > kn - 1) f = kn - 1;
+      wpre[u] = wsrc[static_cast<int64_t>(f) * E];
     }
     const int vpr = kn * EB / 16;                  // 16-byte pieces per row
-    for (int i = tid; i < tpw * vpr; i += 256) {
+#pragma unroll
+    for (int u = 0; u < XMAX; ++u) {
+      int i = tid + u * 256;
+      if (i > tpw * vpr - 1) i = tpw * vpr - 1;
       const int r = i / vpr, v = i - r * vpr;
       int tr = blockIdx.x * tpw + r;
       if (tr > T - 1) tr = T - 1;
-      *reinterpret_cast<uint4*>(xsm + r * xrs + v * 16) =
-          *reinterpret_cast<const uint4*>(x + (static_cast<int64_t>(tr) * ldx + c0) * EB + v * 16);
+      xpre[u] = *reinterpret_cast<const uint4*>(x + (static_cast<int64_t>(tr) * ldx + c0) * EB + v * 16);
     }
-    __syncthreads();
-    const unsigned char* xr = xsm + tl * xrs;
-    const float* wc = wsm + ec * wrs;
-#pragma unroll 4
-    for (int i0 = 0; i0 < kn; i0 += 8) {
-      float f[8];
-      if (BF16) {
-        const uint4 v = *reinterpret_cast<const uint4*>(xr + i0 * 2);
-        const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+  };
+  auto stage = [&](int c0) {
+    const int kn = (d - c0 < kch) ? d - c0 : kch;
+    float* wdst = wsm + ec * wrs;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          f[2 * q] = __uint_as_float(wd[q] << 16);
-          f[2 * q + 1] = __uint_as_float(wd[q] & 0xffff0000u);
+    for (int u = 0; u < WMAX; ++u) {
+      const int f = tl + u * tpw;
+      if (e < E && f < kn) wdst[f] = wpre[u];
+    }
+    const int vpr = kn * EB / 16;
+#pragma unroll
+    for (int u = 0; u < XMAX; ++u) {
+      const int i = tid + u * 256;
+      if (i < tpw * vpr) {
+        const int r = i / vpr, v = i - r * vpr;
+        if (BF16) {      // 8 bf16 -> 8 fp32 (exact), so that the chain below has no conversions in it
+          const uint32_t wd[4] = {xpre[u].x, xpre[u].y, xpre[u].z, xpre[u].w};
+          float4 lo, hi;
+          lo.x = __uint_as_float(wd[0] << 16); lo.y = __uint_as_float(wd[0] & 0xffff0000u);
+          lo.z = __uint_as_float(wd[1] << 16); lo.w = __uint_as_float(wd[1] & 0xffff0000u);
+          hi.x = __uint_as_float(wd[2] << 16); hi.y = __uint_as_float(wd[2] & 0xffff0000u);
+          hi.z = __uint_as_float(wd[3] << 16); hi.w = __uint_as_float(wd[3] & 0xffff0000u);
+          *reinterpret_cast<float4*>(xsm + r * xrs + v * 32) = lo;
+          *reinterpret_cast<float4*>(xsm + r * xrs + v * 32 + 16) = hi;
+        } else {
+          *reinterpret_cast<uint4*>(xsm + r * xrs + v * 16) = xpre[u];
         }
-      } else {
-        const float4 a = *reinterpret_cast<const float4*>(xr + i0 * 4);
-        const float4 b = *reinterpret_cast<const float4*>(xr + i0 * 4 + 16);
-        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
-        f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
       }
-      const float4 wlo = *reinterpret_cast<const float4*>(wc + i0);
-      const float4 whi = *reinterpret_cast<const float4*>(wc + i0 + 4);
-      const float wv[8] = {wlo.x, wlo.y, wlo.z, wlo.w, whi.x, whi.y, whi.z, whi.w};
+    }
+  };
+  fetch(0);
+  for (int c0 = 0; c0 < d; c0 += kch) {
+    const int kn = (d - c0 < kch) ? d - c0 : kch;  // multiple of 8
+    __syncthreads();                               // the previous chunk has been consumed
+    stage(c0);
+    __syncthreads();
+    if (c0 + kch < d) fetch(c0 + kch);
+    // The chain itself: operands of the next 32 features are read from LDS while the 32
+    // dependent FMAs of the current ones run (one wave per SIMD: nothing else hides a wait).
+    const float* xr = reinterpret_cast<const float*>(xsm + tl * xrs);
+    const float* wc = wsm + ec * wrs;
+    float4 xb[8], wb[8];
+    auto read32 = [&](float4 (&xv)[8], float4 (&wv)[8], int i0) {
 #pragma unroll
-      for (int q = 0; q < 8; ++q) acc = __fmaf_rn(f[q], wv[q], acc);
+      for (int q = 0; q < 8; ++q) {
+        xv[q] = *reinterpret_cast<const float4*>(xr + i0 + 4 * q);
+        wv[q] = *reinterpret_cast<const float4*>(wc + i0 + 4 * q);
+      }
+    };
+    const int k32 = kn & ~31;
+    if (k32 > 0) read32(xb, wb, 0);
+    for (int i0 = 0; i0 < k32; i0 += 32) {
+      float4 xn[8], wn[8];
+      const int nxt = (i0 + 32 < k32) ? i0 + 32 : i0;      // (the last round re-reads its own block)
+      read32(xn, wn, nxt);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        acc = __fmaf_rn(xb[q].x, wb[q].x, acc);
+        acc = __fmaf_rn(xb[q].y, wb[q].y, acc);
+        acc = __fmaf_rn(xb[q].z, wb[q].z, acc);
+        acc = __fmaf_rn(xb[q].w, wb[q].w, acc);
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        xb[q] = xn[q];
+        wb[q] = wn[q];
+      }
+    }
+    for (int i0 = k32; i0 < kn; i0 += 4) {                 // the rest of the chunk (a multiple of 8)
+      const float4 xv = *reinterpret_cast<const float4*>(xr + i0);
+      const float4 wv = *reinterpret_cast<const float4*>(wc + i0);
+      acc = __fmaf_rn(xv.x, wv.x, acc);
+      acc = __fmaf_rn(xv.y, wv.y, acc);
+      acc = __fmaf_rn(xv.z, wv.z, acc);
+      acc = __fmaf_rn(xv.w, wv.w, acc);
     }
   }
   if (active) {
@@ -384,12 +445,14 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
     // features per chunk: W chunk <= 32 KiB, x chunk <= 28 KiB (60 KiB of dynamic LDS beside
     // the 4 KiB of static arrays), a multiple of 8, no more than d
     int kch = 8192 / E - 4;
-    const int kx = (28672 / tpw - 16) / eb;
+    const int kx = (28672 / tpw - 16) / 4;         // x is staged as fp32
     if (kx < kch) kch = kx;
     if (d < kch) kch = d;
+    if (kch > GATE_SMALL_WREGS * tpw) kch = GATE_SMALL_WREGS * tpw;                       // what a thread can hold of W_g
+    if (kch > (GATE_SMALL_XREGS * 256 / tpw) * (16 / eb)) kch = (GATE_SMALL_XREGS * 256 / tpw) * (16 / eb);   // and of x
     kch &= ~7;
     if (kch < 8) kch = 8;
-    const size_t lds = static_cast<size_t>(kch + 4) * E * 4 + static_cast<size_t>(tpw) * (kch * eb + 16);
+    const size_t lds = static_cast<size_t>(kch + 4) * E * 4 + static_cast<size_t>(tpw) * (kch * 4 + 16);
     dim3 grid((T + tpw - 1) / tpw), block(256);
     const unsigned char* xb = static_cast<const unsigned char*>(x);
     if (dtype == SCMOE_BF16)
