@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void gate_small_kernel(
     // dependent FMAs of the current ones run (one wave per SIMD: nothing else hides a wait).
     const float* xr = reinterpret_cast<const float*>(xsm + tl * xrs);
     const float* wc = wsm + ec * wrs;
-    float4 xb[8], wb[8];
+    float4 xa[8], wa[8], xb[8], wb[8];                     // two operand sets, used in turn
     auto read32 = [&](float4 (&xv)[8], float4 (&wv)[8], int i0) {
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
@@ -367,24 +367,22 @@ __global__ __launch_bounds__(256) void gate_small_kernel(
         wv[q] = *reinterpret_cast<const float4*>(wc + i0 + 4 * q);
       }
     };
-    const int k32 = kn & ~31;
-    if (k32 > 0) read32(xb, wb, 0);
-    for (int i0 = 0; i0 < k32; i0 += 32) {
-      float4 xn[8], wn[8];
-      const int nxt = (i0 + 32 < k32) ? i0 + 32 : i0;      // (the last round re-reads its own block)
-      read32(xn, wn, nxt);
+    auto fma32 = [&](const float4 (&xv)[8], const float4 (&wv)[8]) {
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
-        acc = __fmaf_rn(xb[q].x, wb[q].x, acc);
-        acc = __fmaf_rn(xb[q].y, wb[q].y, acc);
-        acc = __fmaf_rn(xb[q].z, wb[q].z, acc);
-        acc = __fmaf_rn(xb[q].w, wb[q].w, acc);
+        acc = __fmaf_rn(xv[q].x, wv[q].x, acc);
+        acc = __fmaf_rn(xv[q].y, wv[q].y, acc);
+        acc = __fmaf_rn(xv[q].z, wv[q].z, acc);
+        acc = __fmaf_rn(xv[q].w, wv[q].w, acc);
       }
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        xb[q] = xn[q];
-        wb[q] = wn[q];
-      }
+    };
+    const int k32 = kn & ~63;                              // done 64 features per round
+    if (k32 > 0) read32(xa, wa, 0);
+    for (int i0 = 0; i0 < k32; i0 += 64) {
+      read32(xb, wb, i0 + 32);
+      fma32(xa, wa);
+      read32(xa, wa, (i0 + 64 < k32) ? i0 + 64 : i0);      // (the last round re-reads a block of its own)
+      fma32(xb, wb);
     }
     for (int i0 = k32; i0 < kn; i0 += 4) {                 // the rest of the chunk (a multiple of 8)
       const float4 xv = *reinterpret_cast<const float4*>(xr + i0);
@@ -450,7 +448,7 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
     if (d < kch) kch = d;
     if (kch > GATE_SMALL_WREGS * tpw) kch = GATE_SMALL_WREGS * tpw;                       // what a thread can hold of W_g
     if (kch > (GATE_SMALL_XREGS * 256 / tpw) * (16 / eb)) kch = (GATE_SMALL_XREGS * 256 / tpw) * (16 / eb);   // and of x
-    kch &= ~7;
+    kch &= (kch >= 64) ? ~63 : ~7;                  // whole rounds of the chain loop where possible
     if (kch < 8) kch = 8;
     const size_t lds = static_cast<size_t>(kch + 4) * E * 4 + static_cast<size_t>(tpw) * (kch * 4 + 16);
     dim3 grid((T + tpw - 1) / tpw), block(256);
