@@ -309,14 +309,16 @@ __global__ __launch_bounds__(256) void gate_small_kernel(
       wpre[u] = wsrc[static_cast<int64_t>(f) * E];
     }
     const int vpr = kn * EB / 16;                  // 16-byte pieces per row
+    // 256 / tpw = epad consecutive threads share a row and take consecutive pieces of it, epad
+    // more per pass (epad is a power of two: no division)
+    int tr = blockIdx.x * tpw + tl;
+    if (tr > T - 1) tr = T - 1;
+    const unsigned char* xrow = x + (static_cast<int64_t>(tr) * ldx + c0) * EB;
 #pragma unroll
     for (int u = 0; u < XMAX; ++u) {
-      int i = tid + u * 256;
-      if (i > tpw * vpr - 1) i = tpw * vpr - 1;
-      const int r = i / vpr, v = i - r * vpr;
-      int tr = blockIdx.x * tpw + r;
-      if (tr > T - 1) tr = T - 1;
-      xpre[u] = *reinterpret_cast<const uint4*>(x + (static_cast<int64_t>(tr) * ldx + c0) * EB + v * 16);
+      int v = e + u * epad;
+      if (v > vpr - 1) v = vpr - 1;
+      xpre[u] = *reinterpret_cast<const uint4*>(xrow + v * 16);
     }
   };
   auto stage = [&](int c0) {
@@ -330,9 +332,8 @@ __global__ __launch_bounds__(256) void gate_small_kernel(
     const int vpr = kn * EB / 16;
 #pragma unroll
     for (int u = 0; u < XMAX; ++u) {
-      const int i = tid + u * 256;
-      if (i < tpw * vpr) {
-        const int r = i / vpr, v = i - r * vpr;
+      const int r = tl, v = e + u * epad;
+      if (v < vpr) {
         if (BF16) {      // 8 bf16 -> 8 fp32 (exact), so that the chain below has no conversions in it
           const uint32_t wd[4] = {xpre[u].x, xpre[u].y, xpre[u].z, xpre[u].w};
           float4 lo, hi;
