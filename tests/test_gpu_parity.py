@@ -602,14 +602,18 @@ def test_offload_pool_too_small_is_an_error(oracle):
 
 # --------------------------------------------------- full benchmark sizes, sampled rows
 
-def _full_size(oracle, name, n_sample, k=1, shared=True, normalize=0, pad_weights=False, two_streams=False):
+def _full_size(oracle, name, n_sample, k=1, shared=True, normalize=0, pad_weights=False, two_streams=False,
+               cg_mode=0, residual=False):
     """Routing compared for every token; output rows compared on a seeded sample (the
     oracle evaluates those tokens one by one).  One stream is what bench.py times."""
     L, cfg = inputs.make_config(name)
     T, E = cfg["T"], cfg["E"]
+    if cg_mode:
+        L["Wcg"] = (0.02 * np.random.default_rng(77).standard_normal((2, L["x_cur"].shape[1]))).astype(np.float32)
     C_ = inputs.capacity(T, E, k, cfg["cf"])
     D = DevLayer(L, cfg["dtype"], pad_weights)
-    y, r = run_layer(D, k, C_, shared, normalize, two_streams=two_streams and shared)
+    y, r = run_layer(D, k, C_, shared, normalize, cg_mode=cg_mode, residual=residual,
+                     two_streams=two_streams and shared)
     xg = L["x_prev"] if shared else L["x_cur"]
     rr = oracle.route(xg, L, E, k, C_, normalize)
     assert_routing_equal(r, rr)
@@ -617,7 +621,8 @@ def _full_size(oracle, name, n_sample, k=1, shared=True, normalize=0, pad_weight
     rng = np.random.default_rng(1234)
     dropped = np.nonzero((rr["dst_row"] < 0).any(axis=1))[0]
     tokens = np.unique(np.concatenate([rng.integers(0, T, n_sample), [0, T - 1], dropped[:8]])).astype(np.int32)
-    ref = oracle.layer_rows(L["x_prev"], L["x_cur"], L, rr, tokens, k=k, shared=int(shared))
+    ref = oracle.layer_rows(L["x_prev"], L["x_cur"], L, rr, tokens, k=k, shared=int(shared), cg_mode=cg_mode,
+                            add_residual=int(residual))
     err = relerr(y[tokens], ref)
     assert err <= TOL[cfg["dtype"]], err
     return cfg, r
@@ -650,6 +655,17 @@ def test_full_size_skewed(oracle):
     kept = int(r["offsets"][-1])
     assert cfg["C"] == 1024 and 0.4 * cfg["T"] < kept < 0.75 * cfg["T"]
     assert (r["counts"][:3] == 1024).all()
+
+
+def test_full_size_skewed_other_fused_forms(oracle):
+    """The skewed load (nearly half of the tokens dropped) through the other layers whose
+    decode is fused into the second GEMM: coefficient gate CG-2 with a residual (the shared
+    expert's rows are scaled and added to in place, the routed rows carry the routed
+    coefficient), and the standard top-1 layer (dropped tokens' rows are zeroed)."""
+    _full_size(oracle, "skewed", 64, cg_mode=2, residual=True)
+    _full_size(oracle, "skewed", 64, cg_mode=1)
+    cfg, r = _full_size(oracle, "skewed", 64, shared=False)
+    assert int(r["offsets"][-1]) < 0.75 * cfg["T"]
 
 
 @pytest.mark.parametrize("pad_weights", [True, False])
