@@ -29,6 +29,8 @@ def lib():
         _lib = C.CDLL(path)
         _lib.oracle_gelu.restype = C.c_double
         _lib.oracle_gelu.argtypes = [C.c_double, C.c_int]
+        _lib.oracle_round_to_bf16.restype = C.c_double
+        _lib.oracle_round_to_bf16.argtypes = [C.c_double]
         _lib.oracle_capacity.restype = C.c_int
         _lib.oracle_capacity.argtypes = [C.c_int, C.c_int, C.c_int, C.c_double]
     return _lib
@@ -52,6 +54,11 @@ def num_threads():
 
 def gelu(v, mode=0):
     return lib().oracle_gelu(float(v), int(mode))
+
+
+def round_to_bf16(v):
+    """The rounding the "mimic" mode applies where a bf16 pipeline stores a value."""
+    return lib().oracle_round_to_bf16(float(v))
 
 
 def capacity(T, E, k, cf):

@@ -53,6 +53,9 @@ static double round_to_bf16(double v) {
   return (double)f;
 }
 
+/* The rounding above, exported so that the tests can pin its tie rule and direction. */
+double oracle_round_to_bf16(double v) { return round_to_bf16(v); }
+
 /* GELU.  Exact form: v * Phi(v) with Phi the standard normal CDF written through erf.
  * Tanh form: 0.5 v (1 + tanh( sqrt(2/pi) (v + 0.044715 v^3) )). */
 static double gelu(double v, int mode) {

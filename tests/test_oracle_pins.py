@@ -330,6 +330,39 @@ def test_mimic_mode_rounds_to_bf16(oracle):
                           torch.from_numpy(a).to(torch.bfloat16).float().numpy())
 
 
+def test_round_to_bf16_tie_rule_and_direction(oracle):
+    """The C helper behind mimic mode, bit for bit against torch's fp32 -> bf16 conversion
+    (round to nearest, ties to even) on the cases a wrong rule gets wrong: exact ties with an
+    even and with an odd kept mantissa (truncation, round-half-up and round-half-away all
+    fail one of them), one fp32 ulp above and below a tie, negatives, the carry into the
+    exponent, subnormals, signed zeros, and values already representable."""
+    def f32(bits):
+        return np.array(bits, dtype=np.uint32).view(np.float32)
+    bits = []
+    for hi in (0x3F80, 0x3F81, 0x4049, 0x40FF, 0x7F7E, 0x0001, 0x0000, 0x007F, 0x0080, 0x00FF):
+        for lo in (0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF, 0x4000, 0xC000):
+            for sign in (0, 0x80000000):
+                bits.append(sign | (hi << 16) | lo)
+    bits.append(0x7F7F7FFF)                         # largest value that still rounds to a finite bf16
+    bits.append(0x3FFF8000)                         # tie with an all-ones kept mantissa: carries into the exponent
+    rng = np.random.default_rng(81)
+    bits.extend(int(b) for b in rng.integers(0, 0x7F000000, 4000, dtype=np.int64))
+    bits.extend(int(b) | 0x80000000 for b in rng.integers(0, 0x7F000000, 4000, dtype=np.int64))
+    a = f32(bits)
+    want = torch.from_numpy(a).to(torch.bfloat16).float().numpy()
+    got = np.array([oracle.round_to_bf16(float(v)) for v in a], dtype=np.float64)
+    assert np.isfinite(want).all()
+    assert np.array_equal(got.astype(np.float32).view(np.uint32), want.view(np.uint32))
+    assert np.array_equal(got, want.astype(np.float64))          # and exactly those values as doubles
+    # hand-checked ties: 1 + 2^-8 lies halfway between 1 and 1 + 2^-7 -> the even one (1);
+    # 1 + 3 * 2^-8 lies halfway between 1 + 2^-7 and 1 + 2^-6 -> the even one (1 + 2^-6)
+    assert oracle.round_to_bf16(1.0 + 2.0 ** -8) == 1.0
+    assert oracle.round_to_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    assert oracle.round_to_bf16(-(1.0 + 2.0 ** -8)) == -1.0
+    assert oracle.round_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -23) == 1.0 + 2.0 ** -7
+    assert math.isinf(oracle.round_to_bf16(float("inf"))) and math.isnan(oracle.round_to_bf16(float("nan")))
+
+
 # ------------------------------------------------------------------ layer (Eq. 6, 7, 14-17)
 
 def _layer_bruteforce(L, E, k, C, shared, normalize=0, cg_mode=0, residual=False):
