@@ -76,8 +76,7 @@ def offload_bench(args):
     import torch
     from paper_2404_05019_amd import binding as B
     from paper_2404_05019_amd import inputs
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import DEV, DevLayer
+    from paper_2404_05019_amd.devlayer import DEV, DevLayer
     cfg = inputs.CONFIGS[args.workload]
     T, d, F, E = args.offload, cfg["d"], cfg["F"], cfg["E"]
     L = inputs.make_layer(T=T, d=d, F=F, E=E, dtype="bf16", seed=cfg.get("seed", 5) + 100, biases=True)
@@ -128,8 +127,7 @@ def layers_bench(args):
     import torch
     from paper_2404_05019_amd import binding as B
     from paper_2404_05019_amd import inputs
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import DEV, DevLayer
+    from paper_2404_05019_amd.devlayer import DEV, DevLayer
     L, cfg = inputs.make_config(args.workload)
     T, d, F, E = cfg["T"], cfg["d"], cfg["F"], cfg["E"]
     D = DevLayer(L, cfg["dtype"], pad_weights=args.padded_weights)
@@ -179,8 +177,7 @@ def main():
     import torch
     from paper_2404_05019_amd import binding as B
     from paper_2404_05019_amd import inputs
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import DEV, DevLayer
+    from paper_2404_05019_amd.devlayer import DEV, DevLayer
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.gemm_variant is not None:

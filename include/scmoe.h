@@ -117,8 +117,11 @@ const char* scmoe_status_string(int status);
 /* hipError_t (as int) of the most recent SCMOE_ERR_HIP on the calling thread. */
 int scmoe_last_hip_error(void);
 
-/* Tuning knob, process-wide: tile configuration of the bf16 grouped GEMM behind
- * scmoe_expert_ffn and the layer calls.  0 (default) = chosen per launch: 256x256x64 tiles,
+/* Tuning knob, process-wide and the only state the library keeps between calls (one atomic
+ * integer, read once per launch; no environment variable is consulted): tile configuration of
+ * the bf16 grouped GEMM behind scmoe_expert_ffn and the layer calls.  Meant for benchmarks and
+ * tests; a call that races with a change of the knob uses the old or the new value.
+ * 0 (default) = chosen per launch: 256x256x64 tiles,
  * 8 waves, 2 LDS stages, or 128x128x32 tiles, 2 waves, when the larger tiles would not give
  * every compute unit one; 1 = always 256x256x32, 8 waves, 4 stages; 2 = always 128x128x32.
  * Results agree to bf16 rounding of the same fp32 sums; only speed differs.  Other values
@@ -235,7 +238,8 @@ int scmoe_dispatch(const void* x, int64_t ldx, int32_t dtype, const int32_t* exp
  * identical; they may differ in the last bit from a call without workspace).  NULL, or
  * fewer bytes than asked for: that round runs unsplit.  Calls that may overlap in time
  * need separate workspaces.
- * max_rows <= 64, or max_rows <= 16 E (decode steps; bf16, d and F multiples of 64): the call
+ * max_rows <= 64, or max_rows <= 16 E and max_rows <= 1024 (decode steps; bf16, d and F
+ * multiples of 64): the call
  * is bound by reading the weights, and a weight-streaming kernel replaces the tiled one; up to
  * 64 rows and with a workspace it cuts K into parts so that the whole chip streams (parts
  * summed in a fixed order).
@@ -292,7 +296,11 @@ int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out);
  * = gate(x_prev) -> dispatch -> expert_ffn -> combine(base = SE(x_cur)).
  * The shared expert depends on x_cur only and the routed chain on x_prev only (Sec. 3.2):
  * with stream_aux != NULL the shared expert's GEMMs are enqueued on stream_aux and the
- * routed chain on stream_main, forked and joined with events; with stream_aux == NULL
+ * routed chain on stream_main, forked and joined with events.  Where the output decode is fused
+ * into the routed experts' second GEMM (bf16 MFMA path, k = 1, y apart from the inputs) the join
+ * sits in front of that second GEMM only: gate, encode and the routed first GEMM run beside the
+ * shared expert; otherwise the whole routed chain does and the join sits in front of the
+ * combine kernel.  With stream_aux == NULL
  * everything runs in order on stream_main (and, on the bf16 MFMA path, the first GEMMs of the
  * shared and the routed experts share one launch).  The result is ready on stream_main.
  * desc->k = 1 is ScMoE; desc->k = 2 routes two experts per token on x_prev (ScMoE-2,

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "scmoe.h"
 
 namespace scmoe {
@@ -99,6 +101,8 @@ struct FfnArgs {
   // Scratch of the MFMA path (split-K of the last round of tiles); may be nullptr: no split.
   void* scratch; size_t scratch_bytes;
   bool scratch_zeroed;             // the arrival counters at the start of scratch are zero already
+  // Event the stream waits for between the first and the second GEMM (nullptr: none).  MFMA path.
+  hipEvent_t before_second;
 };
 
 int ffn_generic(const FfnArgs& a, int dtype, hipStream_t stream);
@@ -122,15 +126,15 @@ int ffn_mfma_counter_ints();       // ints at the start of that scratch that mus
 
 // Compute units of the current device (256 on MI355X), cached per device.
 inline int num_cus() {
-  static int cached[64] = {0};
+  static std::atomic<int> cached[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  if (cached[dev] == 0) {
-    int n = 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
-    cached[dev] = n;
+    cached[dev].store(n, std::memory_order_relaxed);
   }
-  return cached[dev];
+  return n;
 }
 
 }  // namespace scmoe

@@ -532,22 +532,16 @@ using CfgB = TileCfg<256, 256, 32, 2, 4, 4>;   // 8 waves, 4 stages, 128 KiB LDS
 #endif
 using CfgS = TileCfg<128, 128, 32, 1, 2, 2>;   // 2 waves, 40 KiB LDS, four workgroups per CU: small problems
 
-// Tile configuration in use: set by scmoe_set_gemm_variant, else SCMOE_GEMM_VARIANT, else 0.
-static int g_variant = -1;
+// Tile configuration in use: 0 unless scmoe_set_gemm_variant has set another.  The one piece of
+// process-wide state of the library: an atomic, read once per launch.
+static std::atomic<int> g_variant{0};
 constexpr int NUM_VARIANTS = 3;
 
-static int gemm_variant() {
-  if (g_variant < 0) {
-    const char* s = getenv("SCMOE_GEMM_VARIANT");
-    int v = s ? atoi(s) : 0;
-    g_variant = (v < 0 || v >= NUM_VARIANTS) ? 0 : v;
-  }
-  return g_variant;
-}
+static int gemm_variant() { return g_variant.load(std::memory_order_relaxed); }
 
 int set_gemm_variant(int v) {
   if (v < 0 || v >= NUM_VARIANTS) return SCMOE_ERR_ARG;
-  g_variant = v;
+  g_variant.store(v, std::memory_order_relaxed);
   return SCMOE_OK;
 }
 
@@ -706,6 +700,14 @@ static GemmArgs second_gemm(const FfnArgs& a, const SplitK& sk) {
   return g;
 }
 
+// Only the second GEMM of a call may depend on work of another stream (a fused output decode
+// adds to rows that the shared expert writes there): the first GEMM runs beside it.
+static int wait_before_second(const FfnArgs& a, hipStream_t stream) {
+  if (a.before_second == nullptr) return SCMOE_OK;
+  const hipError_t e = hipStreamWaitEvent(stream, a.before_second, 0);
+  return e == hipSuccess ? SCMOE_OK : hip_fail(e);
+}
+
 int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
   if (!ffn_mfma_supported(a.d, a.F)) return SCMOE_ERR_ARG;
   if (a.max_rows <= 0) return SCMOE_OK;
@@ -715,12 +717,16 @@ int ffn_mfma_bf16(const FfnArgs& a, hipStream_t stream) {
     const SplitK none;
     const int st1 = launch_gemm_skinny(first_gemm(a, none), true, a.max_rows, a.scratch, a.scratch_bytes, stream);
     if (st1 != SCMOE_OK) return st1;
+    const int stw = wait_before_second(a, stream);
+    if (stw != SCMOE_OK) return stw;
     return launch_gemm_skinny(second_gemm(a, none), false, a.max_rows, a.scratch, a.scratch_bytes, stream);
   }
   SplitK sk;
   int st = prepare_splitk(a, sk, stream);
   if (st != SCMOE_OK) return st;
   st = launch_variant<true>(first_gemm(a, sk), a.max_rows, a.gather ? a.x_rows : a.max_rows, stream);
+  if (st != SCMOE_OK) return st;
+  st = wait_before_second(a, stream);
   if (st != SCMOE_OK) return st;
   return launch_variant<false>(second_gemm(a, sk), a.max_rows, a.max_rows, stream);
 }

@@ -182,7 +182,9 @@ static int copy_routing(const scmoe_desc* D, const LayerWs& w, const scmoe_routi
 // gate -> encode -> experts on `stream`; leaves y_perm, dst_row, gate_w in the workspace.
 // With fused_y != nullptr the second GEMM decodes in its epilogue instead (Sec. 2.2 "output
 // decode"): row r goes to fused_y[src_token[r], :] += gate_w * expert output, on top of what
-// the shared expert has written there; `before_ffn` (optional) is waited for first.
+// the shared expert has written there; `before_ffn` (optional: the shared expert on another
+// stream) is waited for between the first and the second GEMM, so that gate, encode and the
+// first GEMM run beside the shared expert.
 // With shared != nullptr (MFMA path, same stream) the shared expert runs here too: its first
 // GEMM rides in the launch of the routed experts' first GEMM as one more segment.
 // With fused_y and row_coef != nullptr (coefficient gate, Eq. (14)-(17)) the decoded rows are
@@ -216,10 +218,7 @@ static int routed_chain(const scmoe_desc* D, const void* x, int64_t ldx, const s
   a.scratch = w.scratch_bytes ? w.scratch_r : nullptr; a.scratch_bytes = w.scratch_bytes;
   a.scratch_zeroed = chores != nullptr && chores->nzero > 0 && chores->zero_a == a.scratch && a.scratch != nullptr;
   if (fused_y) {
-    if (before_ffn) {
-      hipError_t e = hipStreamWaitEvent(stream, before_ffn, 0);
-      if (e != hipSuccess) return hip_fail(e);
-    }
+    a.before_second = before_ffn;        // only the decoding second GEMM needs the shared expert's rows
     a.y = fused_y; a.ldy = ld_fused;
     a.scatter = w.src_token; a.row_scale = w.gate_w; a.addend = fused_y; a.ldadd = ld_fused;
     if (nothing_below) {

@@ -4,8 +4,6 @@
 #pragma once
 #include "common.hpp"
 
-#include <stdlib.h>
-
 #include <type_traits>
 
 namespace scmoe {

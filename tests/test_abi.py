@@ -164,3 +164,28 @@ def test_zipf_bias_shapes_the_load():
     q /= q.sum()
     assert np.abs(load - q).max() < 0.01
     assert b.dtype == np.float32 and b.max() == 0.0
+
+
+def test_stratified_row_sample_covers_every_row_tile(oracle):
+    """The row sample of the full-size GPU parity tests (gpu_util.stratified_tokens): on a
+    skewed routing with drops, every 128-row block of token order and every 128-row block of
+    every expert's packed segment holds a sampled token, and so do each segment's first and
+    last row."""
+    from gpu_util import stratified_tokens
+    T, E, C_ = 5000, 7, 900
+    rng = np.random.default_rng(5)
+    idx = rng.choice(E, size=(T, 1), p=np.array([.4, .2, .15, .1, .08, .05, .02])).astype(np.int32)
+    counts, offsets, dst_row, src_token = oracle.dispatch(idx, E, C_)
+    rr = dict(offsets=offsets, src_token=src_token, dst_row=dst_row)
+    toks = stratified_tokens(rr, T, E, seed=3)
+    assert len(toks) == len(set(toks.tolist())) and toks.min() >= 0 and toks.max() < T
+    hit = np.zeros(T, bool)
+    hit[toks] = True
+    for b0 in range(0, T, 128):
+        assert hit[b0:b0 + 128].any()
+    assert (dst_row < 0).any() and hit[np.nonzero(dst_row[:, 0] < 0)[0]].any()      # some dropped tokens too
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        assert hit[src_token[lo]] and hit[src_token[hi - 1]]
+        for b0 in range(lo, hi, 128):
+            assert hit[src_token[b0:min(b0 + 128, hi)]].any()
