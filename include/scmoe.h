@@ -218,6 +218,25 @@ int scmoe_dispatch(const void* x, int64_t ldx, int32_t dtype, const int32_t* exp
                    void* stream);
 
 /*
+ * scmoe_dispatch for callers that cannot allocate or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the
+ * workspace, same results bit for bit.  The scratch is a static device array inside the
+ * library of scmoe_dispatch_static_max_bytes bytes (2 MiB; each GPU the library runs on holds
+ * one until the process ends); the call allocates and frees nothing.  A call that would need
+ * more (scmoe_dispatch_workspace_bytes(T, E, k) above that size, i.e. T * k * E beyond about
+ * 67 million) gives SCMOE_ERR_WORKSPACE and launches nothing.  All calls on one GPU share
+ * the array: calls that may overlap in time on one GPU (different streams, different host
+ * threads) race and must be ordered by the caller.
+ */
+int scmoe_dispatch_static(const void* x, int64_t ldx, int32_t dtype, const int32_t* expert_idx,
+                          int32_t T, int32_t d, int32_t E, int32_t k, int32_t capacity,
+                          int32_t* counts, int32_t* offsets, int32_t* dst_row,
+                          int32_t* src_token, void* x_perm, int64_t ld_perm, void* stream);
+
+/* Size in bytes of the static scratch behind scmoe_dispatch_static.  `out` is a host pointer. */
+int scmoe_dispatch_static_max_bytes(size_t* out);
+
+/*
  * Expert computation (Eq. (1); the experts are two-layer MLPs, Sec. 2.1) as a grouped
  * GEMM over packed segments:
  *

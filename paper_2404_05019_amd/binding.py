@@ -19,7 +19,8 @@ MAX_EXPERTS = 64
 
 EXPORTS = ["scmoe_status_string", "scmoe_last_hip_error", "scmoe_set_gemm_variant", "scmoe_padded_ld", "scmoe_capacity",
            "scmoe_gate_top1",
-           "scmoe_gate_top2", "scmoe_gate_topk", "scmoe_dispatch_workspace_bytes", "scmoe_dispatch", "scmoe_expert_ffn",
+           "scmoe_gate_top2", "scmoe_gate_topk", "scmoe_dispatch_workspace_bytes", "scmoe_dispatch", "scmoe_dispatch_static",
+           "scmoe_dispatch_static_max_bytes", "scmoe_expert_ffn",
            "scmoe_expert_ffn_workspace_bytes",
            "scmoe_combine", "scmoe_coef_gate", "scmoe_workspace_bytes", "scmoe_layer_forward",
            "scmoe_offload_pool_bytes", "scmoe_layer_forward_offload", "moe_topk_layer_forward",
@@ -72,6 +73,8 @@ def lib():
         _lib.scmoe_dispatch_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
         _lib.scmoe_dispatch.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i64,
                                         vp, sz, vp]
+        _lib.scmoe_dispatch_static.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, i64, vp]
+        _lib.scmoe_dispatch_static_max_bytes.argtypes = [C.POINTER(sz)]
         _lib.scmoe_expert_ffn.argtypes = [vp, i64, i32, vp, i32, i32, i32, i32, vp, i64, vp, vp, i64, vp, vp, i64,
                                           vp, i64, i32, vp, sz, vp]
         _lib.scmoe_expert_ffn_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
@@ -184,6 +187,19 @@ def scmoe_dispatch(x, expert_idx, E, k, capacity, counts, offsets, dst_row, src_
                                 _ld(x_perm), _ptr(workspace),
                                 0 if workspace is None else workspace.numel() * workspace.element_size(),
                                 _stream(stream)), "scmoe_dispatch")
+
+
+def scmoe_dispatch_static(x, expert_idx, E, k, capacity, counts, offsets, dst_row, src_token, x_perm, stream=None):
+    T, d = x.shape
+    _check(lib().scmoe_dispatch_static(_ptr(x), _ld(x), dtype_code(x), _ptr(expert_idx), T, d, E, k, capacity,
+                                       _ptr(counts), _ptr(offsets), _ptr(dst_row), _ptr(src_token), _ptr(x_perm),
+                                       _ld(x_perm), _stream(stream)), "scmoe_dispatch_static")
+
+
+def scmoe_dispatch_static_max_bytes():
+    out = C.c_size_t(0)
+    _check(lib().scmoe_dispatch_static_max_bytes(C.byref(out)), "scmoe_dispatch_static_max_bytes")
+    return out.value
 
 
 def scmoe_expert_ffn_workspace_bytes(dtype, d, F):

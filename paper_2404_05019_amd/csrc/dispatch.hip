@@ -16,6 +16,15 @@ namespace scmoe {
 
 constexpr int DISP_BLOCK = 256;
 
+// Scratch of scmoe_dispatch_static, the entry point that allocates nothing: the block
+// histograms and block bases that scmoe_dispatch keeps in the caller's workspace live in this
+// array instead.  Every device that loads the library holds its own copy until the process
+// ends.  In host code the name stands for the symbol, not for a device address: the address
+// on the current device comes from hipGetSymbolAddress (static_scratch below) and only that
+// pointer is handed to kernels.
+constexpr size_t DISPATCH_STATIC_BYTES = size_t(2) << 20;
+static __device__ __align__(256) unsigned char scratch[DISPATCH_STATIC_BYTES];
+
 __device__ __forceinline__ int item_expert(const int32_t* __restrict__ expert_idx, int i, int n,
                                            int T, int k, int E, int* t_out, int* j_out) {
   if (i >= n) return -1;
@@ -327,6 +336,49 @@ extern "C" int scmoe_dispatch_workspace_bytes(int32_t T, int32_t E, int32_t k, s
   if (k < 1 || k > SCMOE_MAX_TOPK) return SCMOE_ERR_ARG;
   *out = scmoe::dispatch_ws_bytes(T, E, k);
   return SCMOE_OK;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int static_scratch(void** out) {
+  constexpr int MAXDEV = 64;
+  static std::atomic<void*> ptrs[MAXDEV];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return scmoe::hip_fail(e);
+  if (dev < 0 || dev >= MAXDEV) return SCMOE_ERR_ARG;
+  void* p = ptrs[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scmoe::scratch));
+    if (e != hipSuccess) return scmoe::hip_fail(e);
+    if (p == nullptr) return SCMOE_ERR_HIP;
+    ptrs[dev].store(p, std::memory_order_release);     // (two threads may both look it up: same address)
+  }
+  *out = p;
+  return SCMOE_OK;
+}
+
+extern "C" int scmoe_dispatch_static_max_bytes(size_t* out) {
+  if (!out) return SCMOE_ERR_NULL;
+  *out = scmoe::DISPATCH_STATIC_BYTES;
+  return SCMOE_OK;
+}
+
+extern "C" int scmoe_dispatch_static(const void* x, int64_t ldx, int32_t dtype, const int32_t* expert_idx,
+                                     int32_t T, int32_t d, int32_t E, int32_t k, int32_t capacity,
+                                     int32_t* counts, int32_t* offsets, int32_t* dst_row,
+                                     int32_t* src_token, void* x_perm, int64_t ld_perm, void* stream) {
+  if (T < 0 || E < 1 || E > SCMOE_MAX_EXPERTS) return SCMOE_ERR_SHAPE;
+  if (k < 1 || k > SCMOE_MAX_TOPK) return SCMOE_ERR_ARG;
+  if (static_cast<int64_t>(T) * k > 0x7fffffffLL) return SCMOE_ERR_SHAPE;
+  if (scmoe::dispatch_ws_bytes(T, E, k) > scmoe::DISPATCH_STATIC_BYTES) return SCMOE_ERR_WORKSPACE;
+  void* ws = nullptr;
+  const int st = static_scratch(&ws);
+  if (st != SCMOE_OK) return st;
+  // The kernels write every scratch entry they later read (the block histograms, then the block
+  // bases), so nothing has to be cleared between calls.
+  return scmoe::dispatch(x, ldx, dtype, expert_idx, T, d, E, k, capacity, counts, offsets, dst_row, src_token,
+                         x_perm, ld_perm, ws, scmoe::DISPATCH_STATIC_BYTES, static_cast<hipStream_t>(stream),
+                         nullptr);
 }
 
 extern "C" int scmoe_dispatch(const void* x, int64_t ldx, int32_t dtype, const int32_t* expert_idx,
