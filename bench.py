@@ -18,10 +18,22 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
-# Memory traffic of one grouped-GEMM launch (bytes), from two rocprofv3 --pmc passes
-# (FETCH_SIZE, WRITE_SIZE) scaled by a 1 GiB copy in the same run: see
-# profiles/gemm_bf16_kernel_large_pmc.txt.  Only measured for the workload it is keyed by.
-GEMM_TRAFFIC_BYTES = {"large": 2.4e9}
+
+
+def gemm_traffic_bytes(workload):
+    """Memory traffic of one grouped-GEMM launch (bytes) as measured with rocprofv3 --pmc
+    (FETCH_SIZE and WRITE_SIZE passes, scaled by a 1 GiB copy in the same run): read from the
+    committed summary profiles/gemm_bf16_kernel_<workload>_pmc.txt, which carries the figure in
+    a line `roofline.traffic_bytes_per_launch = <number>`.  None when there is no such summary."""
+    path = os.path.join(ROOT, "profiles", "gemm_bf16_kernel_%s_pmc.txt" % workload)
+    try:
+        with open(path) as f:
+            for line in f:
+                if "roofline.traffic_bytes_per_launch" in line and "=" in line:
+                    return float(line.split("=")[1].split()[0])
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def parse():
@@ -47,6 +59,9 @@ def parse():
     ap.add_argument("--padded-weights", action="store_true",
                     help="store the expert weights with the padded row stride of scmoe_padded_ld "
                          "instead of dense rows")
+    ap.add_argument("--oracle-times", action="store_true",
+                    help="instead of the throughput bench: wall time of the whole CPU oracle layer on every "
+                         "workload with all host threads, and with one thread on the two smallest (no GPU needed)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true",
@@ -167,8 +182,36 @@ def layers_bench(args):
         "layers": res}))
 
 
+def oracle_times(args):
+    """The oracle timed as it stands on the host cores: one whole layer forward per workload."""
+    import ctypes
+    from oracle import cpu as oracle
+    from paper_2404_05019_amd import inputs
+    omp = ctypes.CDLL("libgomp.so.1")
+    nthreads = oracle.num_threads()
+    res = {}
+    for name in ("tiny", "small", "medium", "skewed", "large"):
+        L, cfg = inputs.make_config(name)
+        rec = {}
+        for threads in ([nthreads, 1] if name in ("tiny", "small") else [nthreads]):
+            omp.omp_set_num_threads(threads)
+            t0 = time.perf_counter()
+            _, rr = oracle.layer_forward(L["x_prev"], L["x_cur"], L, k=1, capacity_=cfg["C"])
+            dt = time.perf_counter() - t0
+            rec["threads_%d" % threads] = {"wall_s": round(dt, 3), "tokens_per_s": round(cfg["T"] / dt, 1)}
+        omp.omp_set_num_threads(nthreads)
+        rec["kept_rows"] = int(rr["offsets"][-1])
+        res[name] = rec
+        print("oracle %s: %s" % (name, rec), file=sys.stderr, flush=True)
+    print(json.dumps({"metric": "CPU oracle, whole ScMoE layer forward, wall seconds per workload", "unit": "s",
+                      "host_threads": nthreads, "kind": "oracle", "workloads": res}))
+
+
 def main():
     args = parse()
+    if args.oracle_times:
+        oracle_times(args)
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus,
               file=sys.stderr)
@@ -299,7 +342,7 @@ def main():
         "peak": PEAK_BF16_TFLOPS if is_mfma else 78.6,
         "unit": "TFLOP/s",
         "frac": round(ach_tflops / (PEAK_BF16_TFLOPS if is_mfma else 78.6), 4),
-        "traffic": GEMM_TRAFFIC_BYTES.get(args.workload),
+        "traffic": gemm_traffic_bytes(args.workload),
         "algorithmic_bytes_per_launch": (2 * K * d + 2 * (E + 0) * d * F + K * F) * eb / 2 + K * F * eb / 2,
         "flops_per_launch": ffn_flops / 2,
         "avg_launch_ms": round(ms_ffn / 2, 4),
@@ -315,6 +358,7 @@ def main():
 
     # ---- CPU oracle on a bounded sample of the same workload ------------------------------
     cpu_baseline = None
+    parity = None
     if not args.no_cpu_baseline:
         from oracle import cpu as oracle
         t0 = time.perf_counter()
@@ -329,9 +373,19 @@ def main():
         n -= n % oracle.num_threads() if n > oracle.num_threads() else 0
         sample = rng.integers(0, T, n).astype(np.int32)
         t0 = time.perf_counter()
-        oracle.layer_rows(L["x_prev"], L["x_cur"], L, rr, sample, k=1, shared=1)
+        ref = oracle.layer_rows(L["x_prev"], L["x_cur"], L, rr, sample, k=1, shared=1)
         t_rows = time.perf_counter() - t0
         est_total = t_route + t_rows * (T / n)
+        # the same rows of the layer output that the timed steps left in y, against the oracle's
+        # (after the timed region; both readings of the parity bar)
+        got = y[torch.from_numpy(sample.astype(np.int64)).to(DEV)].float().cpu().numpy().astype(np.float64)
+        tol = 2e-2 if dtype == "bf16" else 1e-4
+        rms = float(np.sqrt(np.mean(ref * ref)))
+        parity = {
+            "rows": int(n), "tol": tol,
+            "max_abs_err_over_max_abs_ref": float(np.abs(got - ref).max() / np.abs(ref).max()),
+            "elementwise_pass_rate": float(np.mean(np.abs(got - ref) <= tol * (np.abs(ref) + rms))),
+        }
         cpu_baseline = {
             "value": round(T / est_total, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
             "kind": "oracle",
@@ -348,7 +402,7 @@ def main():
                    "capacity": C_, "kept_rows": K, "streams": args.streams,
                    "launch": "hip graph replay" if args.graph else "eager",
                    "weight_rows": "padded (scmoe_padded_ld)" if args.padded_weights else "dense"},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "ops": ops, "ceilings": ceilings,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "parity_err": parity, "ops": ops, "ceilings": ceilings,
         "layer_tflops": round((4.0 * (K + T) * d * F) / (ms_per_step * 1e-3) / 1e12, 2),
         "input_generation_s": round(t_gen, 1),
     }

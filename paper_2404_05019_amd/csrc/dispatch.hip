@@ -10,6 +10,7 @@
 //   scan : exclusive prefix over blocks, counts, offsets       -> blockbase[nblk, E]
 //   rank : slot = blockbase + waves before + lanes before      -> dst_row, src_token
 //   rows : x_perm[r, :] = x[src_token[r], :] for r < offsets[E]
+// Up to 131072 items the first three are one launch (dispatch_onepass).
 #include "common.hpp"
 
 namespace scmoe {
@@ -137,116 +138,229 @@ __global__ __launch_bounds__(DISP_BLOCK) void dispatch_rank(
   }
 }
 
-// hist + scan + rank in ONE workgroup of 16 waves for calls of at most DISP_SMALL_ITEMS items
-// (decode steps), where three dependent launches cost more than the work: the items are
-// walked in chunks of 1024 (a lane keeps the experts of its items in registers), once to
-// count and once to rank; same results as the three kernels.  (Measured: 5 us less per layer
-// call up to 1024 tokens, even at 2048; with 8 or 16 chunks one workgroup takes 10-17 us
-// longer than the three kernels.)
-constexpr int DISP_SMALL_THREADS = 1024;
-constexpr int DISP_SMALL_CHUNKS = 2;
-constexpr int DISP_SMALL_ITEMS = DISP_SMALL_THREADS * DISP_SMALL_CHUNKS;
+// hist + scan + rank in ONE launch for calls of at most DISP1_MAX_ITEMS items (every workload of
+// the paper's tables, and decode steps), where three dependent launches cost more than the work.
+// Nothing is handed from workgroup to workgroup: a workgroup owns a block of 1024 consecutive
+// items and counts, by itself, the items of every expert in the whole call and in the blocks
+// before its own, walking all expert indices (128 KB at 32768 items: they come from the L2).
+// The walk is what the kernel costs, so it is made of few instructions per 64 items:
+//  * E <= 16: a lane adds 1 << 4e into a 64-bit register of sixteen 4-bit counters (one item per
+//    lane and vector, so 15 vectors fit before the nibbles are spread into two registers of
+//    8-bit counters: fine up to 255 vectors per wave; the indices of 32 vectors are requested
+//    at a time); the 64 lanes' and 16 waves' counters are
+//    added up once at the end (wave e sums expert e).
+//  * E > 16: one ballot per bit of the expert index per vector; lane L keeps the count of expert L.
+// Integer counts only, so the permutation is the same bit for bit as the three kernels'.  No
+// scratch memory, no atomics, no waiting.
+constexpr int DISP1_THREADS = 1024;
+constexpr int DISP1_WAVES = DISP1_THREADS / 64;
+constexpr int DISP1_MAX_ITEMS = 131072;
+constexpr int DISP1_ROUND = 32;                 // 64-item vectors whose loads are in flight together
 
-__global__ __launch_bounds__(DISP_SMALL_THREADS) void dispatch_small(
-    const int32_t* __restrict__ expert_idx, int T, int k, int E, int capacity, int32_t* __restrict__ counts,
+template <bool NIB, int K>
+__global__ __launch_bounds__(DISP1_THREADS) void dispatch_onepass(
+    const int32_t* __restrict__ expert_idx, int T, int E, int capacity, int32_t* __restrict__ counts,
     int32_t* __restrict__ offsets, int32_t* __restrict__ dst_row, int32_t* __restrict__ src_token,
     const ScanChores ch) {
-  constexpr int NW = DISP_SMALL_THREADS / 64;
-  __shared__ int wcnt[NW][SCMOE_MAX_EXPERTS];     // items per (wave, expert) of the current chunk
-  __shared__ int seen[SCMOE_MAX_EXPERTS];         // items per expert: all (first pass) / in earlier chunks (second)
-  __shared__ int offs[SCMOE_MAX_EXPERTS + 1];
+  constexpr int NW = DISP1_WAVES;
+  constexpr int k = K;
+  static_assert(DISP1_MAX_ITEMS / 64 / NW <= 255 && NW >= 16, "8-bit counters per lane; a wave per expert in the sum");
+  // NIB: [0 = whole call, 1 = before this block][wave][lane] -> four words of 8-bit counters
+  // (expert e: word (e & 1) * 2 + (e >> 3), byte (e >> 1) & 3); else [.][wave][lane = expert] counts.
+  __shared__ int cw[2][NW][64][NIB ? 4 : 1];
+  __shared__ int wown[NW][64];     // items per expert in the wave's own 64 items of the block; then their prefix over waves
+  __shared__ int tot_s[64];        // items of expert e in the whole call
+  __shared__ int seg[64];          // offsets[e]
+  __shared__ int bef[64];          // items of expert e before this block
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
-  if (ch.pair != nullptr && tid == 0) {
-    ch.pair[0] = 0;
-    ch.pair[1] = ch.pair_hi;
-  }
-  for (int i = tid; i < ch.nzero; i += DISP_SMALL_THREADS) {
-    if (ch.zero_a != nullptr) ch.zero_a[i] = 0;
-    if (ch.zero_b != nullptr) ch.zero_b[i] = 0;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (blockIdx.x == 0) {
+    if (ch.pair != nullptr && tid == 0) {
+      ch.pair[0] = 0;
+      ch.pair[1] = ch.pair_hi;
+    }
+    for (int i = tid; i < ch.nzero; i += DISP1_THREADS) {
+      if (ch.zero_a != nullptr) ch.zero_a[i] = 0;
+      if (ch.zero_b != nullptr) ch.zero_b[i] = 0;
+    }
   }
   const int n = T * k;
-  const int nchunk = (n + DISP_SMALL_THREADS - 1) / DISP_SMALL_THREADS;
-  if (tid < SCMOE_MAX_EXPERTS) seen[tid] = 0;
-  __syncthreads();
-  // lanes of this wave that hold the same expert as this lane, and how many of them come before it
-  auto match = [&](int e, bool valid, int& before, int& total) {
-    unsigned long long same = __ballot(valid);
-    for (int b = 0; (1 << b) < E; ++b) {
+  const int nvec = (n + 63) >> 6;
+  const int vb = blockIdx.x * NW;                 // first 64-item vector of this block
+  const int i0 = vb * 64;                         // first item of this block
+  int nb = 0;
+  while ((1 << nb) < E) ++nb;
+  // items of this wave's 64 whose expert is `lane` (lanes >= E count nothing that is used), and
+  // the lanes that hold the same expert as this lane
+  auto count64 = [&](int e, unsigned long long& same) {
+    const bool valid = e >= 0;
+    unsigned long long mine = __ballot(valid);
+    same = mine;
+    for (int b = 0; b < nb; ++b) {
       const unsigned long long bal = __ballot(valid && ((e >> b) & 1));
+      mine &= ((lane >> b) & 1) ? bal : ~bal;
       same &= ((e >> b) & 1) ? bal : ~bal;
     }
-    const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    before = __popcll(same & below);
-    total = __popcll(same);
+    return __popcll(mine);
   };
-  int ev[DISP_SMALL_CHUNKS];
+  // The walk goes through expert_idx in memory order, 64 entries per wave and step: entry
+  // f = t * k + j is item j * T + t.  With k = 1 that is the item order, a vector lies before the
+  // block or not as a whole, and "before this block" is a copy of the counters taken when the
+  // walk reaches the block; with k > 1 a lane adds to a second set of counters when its item
+  // comes before the block's first one.
+  constexpr unsigned long long M4 = 0x0f0f0f0f0f0f0f0full;
+  unsigned long long nib = 0, lo = 0, hi = 0;     // NIB: 4-bit counters since the last spread; 8-bit counters (even, odd experts)
+  unsigned long long b_nib = 0, b_lo = 0, b_hi = 0;
+  int tot = 0, before = 0;                        // !NIB
+  bool snapped = false;                           // k = 1: the counters as they were when the walk reached this block
+  for (int v0 = wave; v0 < nvec; v0 += NW * DISP1_ROUND) {
+    int ev[DISP1_ROUND];
 #pragma unroll
-  for (int q = 0; q < DISP_SMALL_CHUNKS; ++q) {
-    ev[q] = -1;
-    if (q < nchunk) {
-      int t, j;
-      ev[q] = item_expert(expert_idx, q * DISP_SMALL_THREADS + tid, n, T, k, E, &t, &j);
-      int before, total;
-      match(ev[q], ev[q] >= 0, before, total);
-      if (ev[q] >= 0 && before == 0) atomicAdd(&seen[ev[q]], total);   // integer counts: order does not matter
+    for (int u = 0; u < DISP1_ROUND; ++u) {
+      const int f = (v0 + u * NW) * 64 + lane;
+      const int ee = expert_idx[f < n ? f : 0];    // (n > 0 here; entries past the end re-read entry 0)
+      ev[u] = (f < n && ee >= 0 && ee < E) ? ee : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < DISP1_ROUND; ++u) {
+      const int v = v0 + u * NW;
+      if (v < nvec) {                              // wave-uniform
+        bool early = false;                        // k > 1: this lane's item comes before the block
+        if constexpr (K == 1) {
+          if (v >= vb && !snapped) {
+            snapped = true;
+            b_nib = nib; b_lo = lo; b_hi = hi;
+            before = tot;
+          }
+        } else {
+          const int f = v * 64 + lane;
+          early = (f % K) * T + f / K < i0;
+        }
+        if constexpr (NIB) {
+          const unsigned long long inc = static_cast<unsigned long long>(ev[u] >= 0) << ((ev[u] & 15) * 4);
+          nib += inc;
+          if (K > 1) b_nib += early ? inc : 0ull;
+        } else {
+          unsigned long long same;
+          tot += count64(ev[u], same);
+          if (K > 1) before += count64(early ? ev[u] : -1, same);
+        }
+      }
+      if (NIB && (u % 15 == 14 || u == DISP1_ROUND - 1)) {   // before a 4-bit counter can overflow
+        lo += nib & M4;
+        hi += (nib >> 4) & M4;
+        nib = 0;
+        if (K > 1) {
+          b_lo += b_nib & M4;
+          b_hi += (b_nib >> 4) & M4;
+          b_nib = 0;
+        }
+      }
     }
   }
+  if (K == 1 && !snapped) {                        // every vector of this wave lies before the block
+    b_nib = 0; b_lo = lo; b_hi = hi;
+    before = tot;
+  }
+  if constexpr (NIB) {
+    b_lo += b_nib & M4;
+    b_hi += (b_nib >> 4) & M4;
+    cw[0][wave][lane][0] = static_cast<int>(lo); cw[0][wave][lane][1] = static_cast<int>(lo >> 32);
+    cw[0][wave][lane][2] = static_cast<int>(hi); cw[0][wave][lane][3] = static_cast<int>(hi >> 32);
+    cw[1][wave][lane][0] = static_cast<int>(b_lo); cw[1][wave][lane][1] = static_cast<int>(b_lo >> 32);
+    cw[1][wave][lane][2] = static_cast<int>(b_hi); cw[1][wave][lane][3] = static_cast<int>(b_hi >> 32);
+  } else {
+    cw[0][wave][lane][0] = tot;
+    cw[1][wave][lane][0] = before;
+  }
+  // this thread's own item
+  const int i = (vb + wave) * 64 + lane;
+  int t = i, j = 0, e = -1;
+  if constexpr (K == 1) {
+    if (i < n) e = expert_idx[i];
+    if (e >= E) e = -1;
+  } else {
+    e = item_expert(expert_idx, i, n, T, k, E, &t, &j);
+  }
+  unsigned long long same;
+  wown[wave][lane] = count64(e, same);
+  const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  const int rank = __popcll(same & below);
   __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int e = 0; e < E; ++e) {
-      const int c = seen[e] < capacity ? seen[e] : capacity;
-      counts[e] = c;
-      offsets[e] = run;
-      offs[e] = run;
+  if constexpr (NIB) {
+    if (wave < E) {                                // wave e adds up expert e: 16 waves x 64 lanes of 8-bit counters
+      const int word = (wave & 1) * 2 + (wave >> 3), shift = ((wave >> 1) & 3) * 8;
+      int st = 0, sb = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        st += (cw[0][w][lane][word] >> shift) & 255;
+        sb += (cw[1][w][lane][word] >> shift) & 255;
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        st += __shfl_xor(st, off, 64);
+        sb += __shfl_xor(sb, off, 64);
+      }
+      if (lane == 0) {
+        tot_s[wave] = st;
+        bef[wave] = sb;
+      }
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {
+    int tt = 0, bb = 0;
+    if constexpr (NIB) {
+      tt = lane < E ? tot_s[lane] : 0;
+    } else {
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        tt += cw[0][w][lane][0];
+        bb += cw[1][w][lane][0];
+      }
+      bef[lane] = bb;
+    }
+    const int c = (lane < E) ? (tt < capacity ? tt : capacity) : 0;
+    int incl = c;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int up = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += up;
+    }
+    seg[lane] = incl - c;
+    if (blockIdx.x == 0 && lane < E) {
+      counts[lane] = c;
+      offsets[lane] = incl - c;
+      if (lane == E - 1) offsets[E] = incl;
+    }
+  } else if (wave == 1) {
+    int run = 0;                                   // exclusive prefix of the own-vector counts over the waves
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const int c = wown[w][lane];
+      wown[w][lane] = run;
       run += c;
     }
-    offsets[E] = run;
-    offs[E] = run;
   }
   __syncthreads();
-  if (tid < SCMOE_MAX_EXPERTS) seen[tid] = 0;
-#pragma unroll
-  for (int q = 0; q < DISP_SMALL_CHUNKS; ++q) {
-    if (q < nchunk) {
-      for (int c = tid; c < NW * SCMOE_MAX_EXPERTS; c += DISP_SMALL_THREADS) (&wcnt[0][0])[c] = 0;
-      __syncthreads();
-      const int e = ev[q];
-      const bool valid = e >= 0;
-      int before, total;
-      match(e, valid, before, total);
-      if (valid && before == 0) wcnt[wave][e] = total;
-      __syncthreads();
-      const int i = q * DISP_SMALL_THREADS + tid;
-      if (i < n) {
-        const int j = i / T;
-        const int t = i - j * T;
-        int out = -1;
-        if (valid) {
-          int slot = seen[e] + before;
-          for (int w = 0; w < wave; ++w) slot += wcnt[w][e];
-          if (slot < capacity) {
-            out = offs[e] + slot;
-            src_token[out] = t;
-          }
-        }
-        dst_row[static_cast<int64_t>(t) * k + j] = out;
+  if (i < n) {
+    int out = -1;
+    if (e >= 0) {
+      const int slot = bef[e] + wown[wave][e] + rank;
+      if (slot < capacity) {
+        out = seg[e] + slot;
+        src_token[out] = t;
       }
-      __syncthreads();
-      if (tid < E) {
-        int add = 0;
-        for (int w = 0; w < NW; ++w) add += wcnt[w][tid];
-        seen[tid] += add;
-      }
-      // (the next chunk's clearing of wcnt comes after a barrier of its own: see below)
-      __syncthreads();
     }
+    dst_row[static_cast<int64_t>(t) * k + j] = out;
   }
 }
 
-// x_perm[r, :] = x[src_token[r], :], 16 bytes per lane, one wave per row.
+// x_perm[r, :] = x[src_token[r], :], 16 bytes per lane, one wave per row, up to four pieces of a
+// row per lane in flight.  The loads are unconditional (a lane past the end of the row re-reads
+// its last piece and does not store): with loads under a condition the compiler kept the four
+// pieces in LDS instead of registers.
 __global__ __launch_bounds__(256) void gather_rows(const unsigned char* __restrict__ x, int64_t ldx_bytes,
                                                    const int32_t* __restrict__ src_token,
                                                    const int32_t* __restrict__ offsets, int E,
@@ -256,18 +370,21 @@ __global__ __launch_bounds__(256) void gather_rows(const unsigned char* __restri
   const int lane = threadIdx.x & 63;
   const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   const int nwaves = gridDim.x * (blockDim.x >> 6);
+  const int last = row_bytes - 16;
   for (int r = wave; r < K; r += nwaves) {
     const int src = src_token[r];
     const unsigned char* s = x + static_cast<int64_t>(src) * ldx_bytes;
     unsigned char* q = x_perm + static_cast<int64_t>(r) * ldp_bytes;
     for (int c = lane * 16; c < row_bytes; c += 64 * 16 * 4) {
-      uint4 v[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (c + u * 1024 < row_bytes) v[u] = *reinterpret_cast<const uint4*>(s + c + u * 1024);
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (c + u * 1024 < row_bytes) *reinterpret_cast<uint4*>(q + c + u * 1024) = v[u];
+      const int c1 = c + 1024, c2 = c + 2048, c3 = c + 3072;
+      const uint4 v0 = *reinterpret_cast<const uint4*>(s + c);
+      const uint4 v1 = *reinterpret_cast<const uint4*>(s + (c1 < last ? c1 : last));
+      const uint4 v2 = *reinterpret_cast<const uint4*>(s + (c2 < last ? c2 : last));
+      const uint4 v3 = *reinterpret_cast<const uint4*>(s + (c3 < last ? c3 : last));
+      *reinterpret_cast<uint4*>(q + c) = v0;
+      if (c1 < row_bytes) *reinterpret_cast<uint4*>(q + c1) = v1;
+      if (c2 < row_bytes) *reinterpret_cast<uint4*>(q + c2) = v2;
+      if (c3 < row_bytes) *reinterpret_cast<uint4*>(q + c3) = v3;
     }
   }
 }
@@ -301,10 +418,29 @@ int dispatch(const void* x, int64_t ldx, int dtype, const int32_t* expert_idx, i
   if (ws_bytes < dispatch_ws_bytes(T, E, k)) return SCMOE_ERR_WORKSPACE;
   if (T > 0 && !workspace) return SCMOE_ERR_NULL;
   const int nblk = disp_nblk(T, k);
-  const bool small = static_cast<int64_t>(T) * k <= DISP_SMALL_ITEMS;
-  if (small) {
-    hipLaunchKernelGGL(dispatch_small, dim3(1), dim3(DISP_SMALL_THREADS), 0, stream, expert_idx, T, k, E, capacity,
-                       counts, offsets, dst_row, src_token, chores ? *chores : ScanChores{});
+  const int64_t items = static_cast<int64_t>(T) * k;
+  if (items <= DISP1_MAX_ITEMS) {
+    const int blocks = items > 0 ? static_cast<int>((items + DISP1_THREADS - 1) / DISP1_THREADS) : 1;
+    const ScanChores sc = chores ? *chores : ScanChores{};
+#define SCMOE_ONEPASS(NIB, K)                                                                                    \
+  hipLaunchKernelGGL((dispatch_onepass<NIB, K>), dim3(blocks), dim3(DISP1_THREADS), 0, stream, expert_idx, T, E, \
+                     capacity, counts, offsets, dst_row, src_token, sc)
+    if (E <= 16) {
+      switch (k) {
+        case 1: SCMOE_ONEPASS(true, 1); break;
+        case 2: SCMOE_ONEPASS(true, 2); break;
+        case 3: SCMOE_ONEPASS(true, 3); break;
+        default: SCMOE_ONEPASS(true, 4); break;
+      }
+    } else {
+      switch (k) {
+        case 1: SCMOE_ONEPASS(false, 1); break;
+        case 2: SCMOE_ONEPASS(false, 2); break;
+        case 3: SCMOE_ONEPASS(false, 3); break;
+        default: SCMOE_ONEPASS(false, 4); break;
+      }
+    }
+#undef SCMOE_ONEPASS
   } else {
     int32_t* blockhist = static_cast<int32_t*>(workspace);
     int32_t* blockbase = blockhist + static_cast<size_t>(nblk) * E;

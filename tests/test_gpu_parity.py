@@ -110,8 +110,13 @@ def _run_dispatch(x, idx, E, k, C_, dtype, copy=True):
     (5000, 8, 1, 700, 64, "bf16"), (5000, 16, 2, 500, 40, "f32"), (1025, 64, 2, 40, 8, "bf16"),
     (4096, 7, 2, 100000, 8, "f32"), (300, 1, 1, 17, 8, "bf16"), (3000, 8, 3, 900, 16, "bf16"),
     (1000, 6, 4, 500, 8, "f32"), (257, 3, 3, 300, 8, "f32"),
-    # one-workgroup form (at most 2048 items): one chunk, the chunk boundary, both chunks full, one item past it
-    (1024, 8, 1, 100, 8, "f32"), (1025, 5, 1, 300, 8, "f32"), (1024, 16, 2, 90, 8, "bf16"), (683, 9, 3, 200, 8, "f32")])
+    # block boundaries of the one-launch form (blocks of 1024 items): one block, one item past it, two full blocks
+    (1024, 8, 1, 100, 8, "f32"), (1025, 5, 1, 300, 8, "f32"), (1024, 16, 2, 90, 8, "bf16"), (683, 9, 3, 200, 8, "f32"),
+    # fewer tokens than a wave has lanes with several choices (an item vector spans choices), 64 experts, 33 experts
+    (5, 4, 4, 3, 8, "f32"), (40, 6, 3, 100, 8, "bf16"), (4097, 64, 4, 200, 8, "f32"), (9000, 33, 1, 250, 8, "bf16"),
+    # the one-launch form's limit of 131072 items: at it, just past it (three kernels with scratch), far past it
+    (131072, 16, 1, 9000, 8, "bf16"), (65536, 8, 2, 20000, 8, "f32"), (131073, 16, 1, 9000, 8, "bf16"),
+    (43691, 5, 3, 30000, 8, "f32"), (70000, 7, 2, 15000, 8, "bf16"), (400000, 12, 1, 30000, 8, "bf16")])
 def test_dispatch_parity(oracle, T, E, k, C_, d, dtype):
     rng = np.random.default_rng(T * 7 + E)
     x = inputs.quantize(rng.standard_normal((T, d)), dtype)
