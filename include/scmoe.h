@@ -17,8 +17,9 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Argument checks
  *    run synchronously on the host; kernels are enqueued on the stream and the call returns
  *    without synchronising.
- *  - The return value is a status code (SCMOE_OK == 0).  On an error nothing is launched.
- *    No exception and no abort crosses the boundary.
+ *  - The return value is a status code (SCMOE_OK == 0).  On an error nothing is launched (one
+ *    exception, stated at the entry: the expert pool of the offload calls turning out too
+ *    small).  No exception and no abort crosses the boundary.
  *  - Matrices are row-major.  `ld*` arguments are row strides in ELEMENTS.
  *  - `dtype` (SCMOE_F32 or SCMOE_BF16) is the storage type of activations and of the FFN
  *    weight matrices.  Gate weights W_g, gate bias, FFN biases, gate_w and probs are
@@ -363,15 +364,47 @@ int scmoe_offload_pool_bytes(const scmoe_desc* desc, int32_t pool_experts, size_
  *                                shared expert ("Offload", blocking migration).
  *
  * The call synchronises stream_main once on the host (the host reads the per-expert counts to
- * issue the copies).  SCMOE_ERR_WORKSPACE if more experts are selected than the pool holds.
+ * issue the copies).  SCMOE_ERR_WORKSPACE if more experts are selected than the pool holds:
+ * that is known only once the counts are on the host, so for this one error gate routing and
+ * input encode HAVE run and stream_main HAS been synchronised when the call returns (nothing
+ * else is enqueued); every other error is found before anything is launched.
  * Result: the same from call to call; equal to scmoe_layer_forward's on the same inputs up
  * to rounding (the two launch their GEMMs differently, see there).
+ * This call is scmoe_offload_begin followed at once by scmoe_offload_finish: only the shared
+ * expert is then available to hide the copies behind.  Callers with work of their own to put
+ * in between (the attention and MLP of the block pair, Sec. 5.3) use the two calls below.
  */
 int scmoe_layer_forward_offload(const scmoe_desc* desc, const void* x_prev, int64_t ld_prev,
                                 const void* x_cur, int64_t ld_cur, const scmoe_weights* w,
                                 void* expert_pool, int32_t pool_experts, int32_t async_copy,
                                 int32_t* host_plan, void* y, int64_t ldy, void* workspace,
                                 size_t ws_bytes, void* stream_main, void* stream_copy);
+
+/*
+ * The two halves of scmoe_layer_forward_offload (same arguments, same meaning).
+ *
+ * scmoe_offload_begin: gate routing and input encode on x_prev, the per-expert counts to
+ * host_plan, one host synchronisation of stream_main, then the copies of exactly the selected
+ * experts into the pool are ISSUED (on stream_copy behind an event when async_copy = 1, else on
+ * stream_main) and the call returns.  Whatever the caller enqueues on stream_main after it runs
+ * while the experts migrate: this window between "selection known" and "experts needed" is the
+ * mechanism of Sec. 5.3 / appendix A.3.  SCMOE_ERR_WORKSPACE as described above.
+ *
+ * scmoe_offload_finish: the shared expert on x_cur, then (behind the copies) the routed
+ * experts from the pool, output decode and merge into y.  Must follow a scmoe_offload_begin
+ * with the same desc, weights, pool, host_plan, workspace and streams; between the two calls
+ * the caller must leave the workspace, the pool and host_plan alone (they carry the routing
+ * and the migrating experts) and must enqueue nothing on stream_copy.  No host synchronisation.
+ */
+int scmoe_offload_begin(const scmoe_desc* desc, const void* x_prev, int64_t ld_prev,
+                        const scmoe_weights* w, void* expert_pool, int32_t pool_experts,
+                        int32_t async_copy, int32_t* host_plan, void* workspace, size_t ws_bytes,
+                        void* stream_main, void* stream_copy);
+int scmoe_offload_finish(const scmoe_desc* desc, const void* x_prev, int64_t ld_prev,
+                         const void* x_cur, int64_t ld_cur, const scmoe_weights* w,
+                         void* expert_pool, int32_t pool_experts, int32_t async_copy,
+                         const int32_t* host_plan, void* y, int64_t ldy, void* workspace,
+                         size_t ws_bytes, void* stream_main, void* stream_copy);
 
 /*
  * Standard top-k MoE layer on the current-layer representation (Eq. (1)-(4); k = 2 is the

@@ -23,7 +23,7 @@ EXPORTS = ["scmoe_status_string", "scmoe_last_hip_error", "scmoe_set_gemm_varian
            "scmoe_dispatch_static_max_bytes", "scmoe_expert_ffn",
            "scmoe_expert_ffn_workspace_bytes",
            "scmoe_combine", "scmoe_coef_gate", "scmoe_workspace_bytes", "scmoe_layer_forward",
-           "scmoe_offload_pool_bytes", "scmoe_layer_forward_offload", "moe_topk_layer_forward",
+           "scmoe_offload_pool_bytes", "scmoe_layer_forward_offload", "scmoe_offload_begin", "scmoe_offload_finish", "moe_topk_layer_forward",
            "moe_top2_layer_forward"]
 
 
@@ -86,6 +86,10 @@ def lib():
         _lib.scmoe_offload_pool_bytes.argtypes = [C.POINTER(Desc), i32, C.POINTER(sz)]
         _lib.scmoe_layer_forward_offload.argtypes = [C.POINTER(Desc), vp, i64, vp, i64, C.POINTER(Weights), vp, i32,
                                                      i32, vp, vp, i64, vp, sz, vp, vp]
+        _lib.scmoe_offload_begin.argtypes = [C.POINTER(Desc), vp, i64, C.POINTER(Weights), vp, i32, i32, vp, vp, sz,
+                                             vp, vp]
+        _lib.scmoe_offload_finish.argtypes = [C.POINTER(Desc), vp, i64, vp, i64, C.POINTER(Weights), vp, i32, i32, vp,
+                                              vp, i64, vp, sz, vp, vp]
         _lib.moe_topk_layer_forward.argtypes = [C.POINTER(Desc), vp, i64, C.POINTER(Weights), vp, i64,
                                                 C.POINTER(RoutingOut), vp, sz, vp]
         _lib.moe_top2_layer_forward.argtypes = _lib.moe_topk_layer_forward.argtypes
@@ -284,6 +288,25 @@ def scmoe_layer_forward_offload(desc, x_prev, x_cur, weights, expert_pool, pool_
         pool_experts, 1 if async_copy else 0, _ptr(host_plan), _ptr(y), _ld(y), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream_main),
         None if stream_copy is None else _stream(stream_copy)), "scmoe_layer_forward_offload")
+
+
+def scmoe_offload_begin(desc, x_prev, weights, expert_pool, pool_experts, host_plan, workspace, async_copy=True,
+                        stream_main=None, stream_copy=None):
+    assert host_plan.dtype == torch.int32 and not host_plan.is_cuda
+    _check(lib().scmoe_offload_begin(
+        C.byref(desc), _ptr(x_prev), _ld(x_prev), C.byref(weights), _ptr(expert_pool), pool_experts,
+        1 if async_copy else 0, _ptr(host_plan), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream_main), None if stream_copy is None else _stream(stream_copy)), "scmoe_offload_begin")
+
+
+def scmoe_offload_finish(desc, x_prev, x_cur, weights, expert_pool, pool_experts, host_plan, y, workspace,
+                         async_copy=True, stream_main=None, stream_copy=None):
+    assert host_plan.dtype == torch.int32 and not host_plan.is_cuda
+    _check(lib().scmoe_offload_finish(
+        C.byref(desc), _ptr(x_prev), _ld(x_prev), _ptr(x_cur), _ld(x_cur), C.byref(weights), _ptr(expert_pool),
+        pool_experts, 1 if async_copy else 0, _ptr(host_plan), _ptr(y), _ld(y), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream_main),
+        None if stream_copy is None else _stream(stream_copy)), "scmoe_offload_finish")
 
 
 def moe_topk_layer_forward(desc, x, weights, y, workspace, routing=None, stream=None):

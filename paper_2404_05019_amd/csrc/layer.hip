@@ -477,11 +477,9 @@ extern "C" int scmoe_offload_pool_bytes(const scmoe_desc* D, int32_t pool_expert
   return SCMOE_OK;
 }
 
-extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_prev, int64_t ld_prev,
-                                           const void* x_cur, int64_t ld_cur, const scmoe_weights* W,
-                                           void* expert_pool, int32_t pool_experts, int32_t async_copy,
-                                           int32_t* host_plan, void* y, int64_t ldy, void* workspace,
-                                           size_t ws_bytes, void* stream_main, void* stream_copy) {
+// Checks shared by the three offload entry points.
+static int check_offload(const scmoe_desc* D, const scmoe_weights* W, const void* expert_pool, int32_t pool_experts,
+                         int32_t async_copy, const int32_t* host_plan, const void* workspace, size_t ws_bytes) {
   SCMOE_TRY(check_desc(D, 1, SCMOE_MAX_TOPK));
   SCMOE_TRY(check_weights(D, W, true));
   if ((W->ld_w1 != 0 && W->ld_w1 != D->d) || (W->ld_w2 != 0 && W->ld_w2 != D->F))
@@ -489,13 +487,37 @@ extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_pr
   if (async_copy != 0 && async_copy != 1) return SCMOE_ERR_ARG;
   if (pool_experts < 1 || pool_experts > D->E) return SCMOE_ERR_SHAPE;
   if (D->T == 0) return SCMOE_OK;
-  if (!x_prev || !x_cur || !y || !workspace || !expert_pool || !host_plan) return SCMOE_ERR_NULL;
-  if (!view_ok(x_prev, ld_prev, D->d, D->dtype) || !view_ok(x_cur, ld_cur, D->d, D->dtype) ||
-      !view_ok(y, ldy, D->d, D->dtype) || !aligned16(workspace) ||
-      (reinterpret_cast<uintptr_t>(expert_pool) & 255u) != 0)
-    return SCMOE_ERR_SHAPE;
+  if (!workspace || !expert_pool || !host_plan) return SCMOE_ERR_NULL;
+  if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(expert_pool) & 255u) != 0) return SCMOE_ERR_SHAPE;
+  if (ws_bytes < carve(D, nullptr, true).total) return SCMOE_ERR_WORKSPACE;
+  return SCMOE_OK;
+}
+
+// Experts with kept rows take pool slots in expert order, so the packed rows (ordered by
+// expert) are the segments of the slots in slot order.  Returns the number of slots in use,
+// or -1 when there are more than `pool_experts`; offs_c (if given) receives their segment bounds.
+static int offload_plan(const int32_t* counts, int E, int pool_experts, int* slot_expert, int32_t* offs_c) {
+  int m = 0;
+  if (offs_c) offs_c[0] = 0;
+  for (int e = 0; e < E; ++e) {
+    if (counts[e] > 0) {
+      if (m == pool_experts) return -1;
+      slot_expert[m] = e;
+      if (offs_c) offs_c[m + 1] = offs_c[m] + counts[e];
+      ++m;
+    }
+  }
+  return m;
+}
+
+extern "C" int scmoe_offload_begin(const scmoe_desc* D, const void* x_prev, int64_t ld_prev, const scmoe_weights* W,
+                                   void* expert_pool, int32_t pool_experts, int32_t async_copy, int32_t* host_plan,
+                                   void* workspace, size_t ws_bytes, void* stream_main, void* stream_copy) {
+  SCMOE_TRY(check_offload(D, W, expert_pool, pool_experts, async_copy, host_plan, workspace, ws_bytes));
+  if (D->T == 0) return SCMOE_OK;
+  if (!x_prev) return SCMOE_ERR_NULL;
+  if (!view_ok(x_prev, ld_prev, D->d, D->dtype)) return SCMOE_ERR_SHAPE;
   const LayerWs w = carve(D, workspace, true);
-  if (ws_bytes < w.total) return SCMOE_ERR_WORKSPACE;
   const OffloadPool pool = carve_pool(D, expert_pool, pool_experts);
   hipStream_t sm = static_cast<hipStream_t>(stream_main);
   hipStream_t sc = static_cast<hipStream_t>(stream_copy);
@@ -522,20 +544,11 @@ extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_pr
   he = hipStreamSynchronize(sm);                // the host needs the counts to issue the copies
   if (he != hipSuccess) return hip_fail(he);
 
-  // 2. Plan: present experts take pool slots in expert order, so the packed rows (ordered by
-  //    expert) are the segments of the slots in slot order.
+  // 2. Plan and migration.
   int32_t* offs_c = host_plan + E;
-  int m = 0;
-  offs_c[0] = 0;
   int slot_expert[SCMOE_MAX_EXPERTS];
-  for (int e = 0; e < E; ++e) {
-    if (host_plan[e] > 0) {
-      if (m == pool_experts) return SCMOE_ERR_WORKSPACE;   // more experts selected than the pool holds
-      slot_expert[m] = e;
-      offs_c[m + 1] = offs_c[m] + host_plan[e];
-      ++m;
-    }
-  }
+  const int m = offload_plan(host_plan, E, pool_experts, slot_expert, offs_c);
+  if (m < 0) return SCMOE_ERR_WORKSPACE;        // more experts selected than the pool holds
   hipStream_t cs = async ? sc : sm;
   if (async) {
     he = hipStreamWaitEvent(sc, ev->fork, 0);
@@ -563,13 +576,38 @@ extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_pr
   }
   he = hipMemcpyAsync(w.offsets_c, offs_c, static_cast<size_t>(m + 1) * 4, hipMemcpyHostToDevice, cs);
   if (he != hipSuccess) return hip_fail(he);
+  return SCMOE_OK;
+}
+
+extern "C" int scmoe_offload_finish(const scmoe_desc* D, const void* x_prev, int64_t ld_prev, const void* x_cur,
+                                    int64_t ld_cur, const scmoe_weights* W, void* expert_pool, int32_t pool_experts,
+                                    int32_t async_copy, const int32_t* host_plan, void* y, int64_t ldy,
+                                    void* workspace, size_t ws_bytes, void* stream_main, void* stream_copy) {
+  SCMOE_TRY(check_offload(D, W, expert_pool, pool_experts, async_copy, host_plan, workspace, ws_bytes));
+  if (D->T == 0) return SCMOE_OK;
+  if (!x_prev || !x_cur || !y) return SCMOE_ERR_NULL;
+  if (!view_ok(x_prev, ld_prev, D->d, D->dtype) || !view_ok(x_cur, ld_cur, D->d, D->dtype) ||
+      !view_ok(y, ldy, D->d, D->dtype))
+    return SCMOE_ERR_SHAPE;
+  const LayerWs w = carve(D, workspace, true);
+  const OffloadPool pool = carve_pool(D, expert_pool, pool_experts);
+  hipStream_t sm = static_cast<hipStream_t>(stream_main);
+  hipStream_t sc = static_cast<hipStream_t>(stream_copy);
+  const bool async = async_copy == 1 && stream_copy != nullptr && sc != sm;
+  const int E = D->E;
+  int slot_expert[SCMOE_MAX_EXPERTS];
+  const int m = offload_plan(host_plan, E, pool_experts, slot_expert, nullptr);
+  if (m < 0) return SCMOE_ERR_WORKSPACE;
+  hipError_t he;
+  EventPair* ev = nullptr;
   if (async) {
-    he = hipEventRecord(ev->join, sc);
+    SCMOE_TRY(get_events(&ev));
+    he = hipEventRecord(ev->join, sc);          // behind the copies that scmoe_offload_begin put on this stream
     if (he != hipSuccess) return hip_fail(he);
   }
 
-  // 3. Shared expert on the current-layer representation: resident, and it is the computation
-  //    the asynchronous migration hides behind.
+  // 3. Shared expert on the current-layer representation: resident; under asynchronous
+  //    migration it runs while the copies are still arriving.
   hipLaunchKernelGGL(set_pair, dim3(1), dim3(64), 0, sm, w.offsets_shared, 0, D->T);
   SCMOE_TRY(launch_status());
   FfnArgs se{};
@@ -590,6 +628,7 @@ extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_pr
     if (he != hipSuccess) return hip_fail(he);
   }
   if (m > 0) {
+    const bool gol = gather_on_load(D);
     FfnArgs a{};
     a.x = gol ? x_prev : w.x_perm;
     a.ldx = gol ? ld_prev : D->d;
@@ -606,6 +645,24 @@ extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_pr
   }
   return combine(w.y_perm, D->d, D->dtype, w.dst_row, w.gate_w, D->T, D->d, D->k, w.s, D->d, nullptr, 0,
                  D->cg_mode != SCMOE_CG_NONE ? w.coef : nullptr, y, ldy, sm);
+}
+
+extern "C" int scmoe_layer_forward_offload(const scmoe_desc* D, const void* x_prev, int64_t ld_prev,
+                                           const void* x_cur, int64_t ld_cur, const scmoe_weights* W,
+                                           void* expert_pool, int32_t pool_experts, int32_t async_copy,
+                                           int32_t* host_plan, void* y, int64_t ldy, void* workspace,
+                                           size_t ws_bytes, void* stream_main, void* stream_copy) {
+  // every argument check of both halves comes before anything is enqueued
+  SCMOE_TRY(check_offload(D, W, expert_pool, pool_experts, async_copy, host_plan, workspace, ws_bytes));
+  if (D->T == 0) return SCMOE_OK;
+  if (!x_prev || !x_cur || !y) return SCMOE_ERR_NULL;
+  if (!view_ok(x_prev, ld_prev, D->d, D->dtype) || !view_ok(x_cur, ld_cur, D->d, D->dtype) ||
+      !view_ok(y, ldy, D->d, D->dtype))
+    return SCMOE_ERR_SHAPE;
+  SCMOE_TRY(scmoe_offload_begin(D, x_prev, ld_prev, W, expert_pool, pool_experts, async_copy, host_plan, workspace,
+                                ws_bytes, stream_main, stream_copy));
+  return scmoe_offload_finish(D, x_prev, ld_prev, x_cur, ld_cur, W, expert_pool, pool_experts, async_copy, host_plan,
+                              y, ldy, workspace, ws_bytes, stream_main, stream_copy);
 }
 
 extern "C" int moe_topk_layer_forward(const scmoe_desc* D, const void* x, int64_t ldx,

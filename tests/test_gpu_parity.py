@@ -576,6 +576,18 @@ def _offload_case(oracle, T, E, k, C_, pool_experts, async_copy, seed):
                                    normalize=0)
     assert relerr(to_host(y), ref) <= TOL["bf16"]
     assert np.array_equal(plan[:E].numpy(), rr["counts"])
+    # The two halves as calls of their own, with work of the caller on the main stream in between
+    # (the window the migration hides in): the same bits as the single call.
+    y2 = torch.full_like(y, float("nan"))
+    filler_a = torch.randn((512, 512), device=DEV)
+    pool.fill_(0x7f)
+    B.scmoe_offload_begin(desc, D.x_prev, wts, pool, pool_experts, plan, ws, async_copy=async_copy,
+                          stream_copy=copy_stream)
+    filler_b = filler_a @ filler_a
+    B.scmoe_offload_finish(desc, D.x_prev, D.x_cur, wts, pool, pool_experts, plan, y2, ws, async_copy=async_copy,
+                           stream_copy=copy_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, first) and bool(torch.isfinite(filler_b).all())
     return plan[:E].numpy()
 
 
@@ -603,6 +615,12 @@ def test_offload_pool_too_small_is_an_error(oracle):
     y = torch.empty((500, D.d), dtype=D.tdtype, device=DEV)
     with pytest.raises(B.ScmoeError) as e:                # 500 tokens select more than 2 of 8 experts
         B.scmoe_layer_forward_offload(desc, D.x_prev, D.x_cur, wts, pool, 2, plan, y, ws)
+    assert e.value.status == 4
+    with pytest.raises(B.ScmoeError) as e:
+        B.scmoe_offload_begin(desc, D.x_prev, wts, pool, 2, plan, ws)
+    assert e.value.status == 4 and int(plan[:8].sum()) == 500     # (the counts are on the host by then)
+    with pytest.raises(B.ScmoeError) as e:                # and a finish on such a plan refuses too
+        B.scmoe_offload_finish(desc, D.x_prev, D.x_cur, wts, pool, 2, plan, y, ws)
     assert e.value.status == 4
     torch.cuda.synchronize()
 
