@@ -82,10 +82,10 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 
   // ---- tile schedule ------------------------------------------------------------------------
   const int nk_all = p.Kd / BK;
-  TileSchedule<BM, BN, ACT ? CFG::GM_FIRST : CFG::GM_SECOND> sched(p, nk_all, p.splitk_part != nullptr);
+  TileSchedule<BM, BN, ACT ? CFG::GM_FIRST : CFG::GM_SECOND> sched(p, nk_all, p.splitk_part != nullptr, CFG::WAVES);
   const int nslots = sched.nslots;
-  int it = blockIdx.x >> 3;                // work item: a tile, or one K-part of a tile of the last round
-  if (it >= sched.nitems) return;
+  int it = blockIdx.x >> 3;                // work item: a tile, one K-part of a tile of the last round, or a finish item
+  if (it >= sched.ngemm + sched.nfin) return;
   int nk = nk_all;                         // k-tiles of the current item
 
   // ---- per-lane source addresses of the direct-to-LDS loads -------------------------------
@@ -250,6 +250,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     }
     set_ptrs(e, row0, row_end, n0, kb);
   };
+  if (it < sched.ngemm) {
   setup(it);
   issue_prologue();
   for (;;) {
@@ -340,8 +341,8 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 
     // ---- next tile: its first k-tiles are requested before this tile's epilogue -----------
     const int itn = it + nslots;
-    const bool more = itn < sched.nitems;
-    const int crow0 = row0, crow_end = row_end, cn0 = n0, cpart = part, cw = it - sched.full;
+    const bool more = itn < sched.ngemm;
+    const int crow0 = row0, crow_end = row_end, cn0 = n0, cpart = part, cw = it;   // (a part is item cw < npart)
     unsigned char* const cC = (XSEG && e == p.E) ? p.xC : p.C;        // output of the current tile's segment
     const int64_t cldc = (XSEG && e == p.E) ? p.xldc : p.ldc;
     lds_barrier();                    // every wave holds its last fragments: LDS is free
@@ -388,18 +389,15 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       issue_prologue();
     }
 
-    // ---- split-K items: leave the partial sums in scratch; the last part to arrive adds all
-    // parts up in part order (so the result does not depend on the arrival order) and goes
-    // on to the epilogue, the others are done.  No workgroup waits for another one.
-    // The partial sums and the counter move with relaxed device-scope atomics, which go past
-    // the caches that are not shared by the whole device, ordered by a plain wait for the
-    // stores; device-scope fences would write back and invalidate the whole L2 of the XCD on
-    // every use, which costs more than the split saves.
-    bool finish = true;
+    // ---- split-K items: leave the partial sums in scratch and count the part in; the finish
+    // items at the end of the launch add the parts up.  The partial sums and the counter move
+    // with relaxed device-scope accesses (sc1: past the caches that are not shared by the whole
+    // device), ordered by a plain wait for the stores; device-scope fences would write back and
+    // invalidate the whole L2 of the XCD on every use, which costs more than the split saves.
+    const bool finish = cpart < 0;
     if (cpart >= 0) {
       constexpr int TILE = BM * BN;
       constexpr int FRAGS = MI * NJ;                                  // 16-byte pieces (accumulators) per lane
-      const int S = sched.S;
       const size_t slot0 = static_cast<size_t>(sched.xcd) * nslots;   // this XCD's scratch slots
       // accumulator (i, j) of wave w and lane l sits at float4 index (w * FRAGS + i * NJ + j) * 64 + l
       float* mine = p.splitk_part + (slot0 + cw) * TILE + ((wave * FRAGS) * 64 + lane) * 4;
@@ -408,34 +406,9 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 #pragma unroll
         for (int j = 0; j < NJ; ++j) store16_device_scope(mine + ((i * NJ + j) * 64) * 4, acc[i][j]);
       wait_vm(std::integral_constant<int, 0>{});                      // this wave's stores have been performed
-      lds_barrier();
-      int* flag = reinterpret_cast<int*>(smem + NS * STAGE);          // first word of wave 0's epilogue patch
-      if (tid == 0) {
-        int* cnt = p.splitk_count + slot0 + cw / S;
-        const int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old == S - 1)                                             // all parts are in: ready for the next launch
-          __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *flag = old;
-      }
-      lds_barrier();
-      const int old = *flag;
-      lds_barrier();                                                  // the patch is reused below
-      finish = old == S - 1;
-      if (finish) {
-        const float* first = p.splitk_part + (slot0 + (cw / S) * S) * TILE + ((wave * FRAGS) * 64 + lane) * 4;
-        for (int q = 0; q < S; ++q) {
-          const float* src = first + static_cast<size_t>(q) * TILE;
-#pragma unroll
-          for (int i = 0; i < MI; ++i) {
-            f32x4_t t[NJ];
-            static_assert(NJ == 4, "four pieces 1 KiB apart per load group");
-            load4x16_device_scope(src + ((i * NJ) * 64) * 4, t[0], t[1], t[2], t[3]);
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[i][j] = (q == 0) ? t[j] : acc[i][j] + t[j];
-          }
-        }
-        if (dec) decode_loads();
-      }
+      lds_barrier();                                                  // ... and every wave's
+      if (tid == 0)
+        __hip_atomic_fetch_add(p.splitk_count + slot0 + cw / sched.S, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // ---- epilogue: activation, bf16; rows re-assembled in LDS, 16-byte stores ----------------
@@ -520,6 +493,101 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     }
     if (!more) break;
     it = itn;
+  }
+  it += nslots;
+  }
+
+  // ---- finish items: one per wave tile of a tile that was cut along K ------------------------
+  // The parts are added up in part order (the result does not depend on who arrived when) by a
+  // workgroup that has nothing else left to do: each of its waves takes MI / WAVES row-subtiles
+  // of the wave tile, so the 256 KiB of a tile's partial sums per part are read by all waves of
+  // WAVES workgroups at once.  The parts were counted in long ago (they are the first items of
+  // their workgroups, which have lower ids and started earlier); the count is checked anyway,
+  // with a bounded wait, so that no wave can be left waiting for good.
+  for (; it < sched.ngemm + sched.nfin; it += nslots) {
+    constexpr int TILE = BM * BN, FRAGS = MI * NJ, FS = CFG::WAVES, RPW = MI / CFG::WAVES;
+    static_assert(MI % CFG::WAVES == 0 && NJ == 4, "row-subtiles of a wave tile are shared out among the waves");
+    const int f = it - sched.ngemm;
+    const int lt = f / FS, region = f - lt * FS;                      // cut tile (0 .. rem-1), wave tile of it
+    const int S = sched.S;
+    const size_t slot0 = static_cast<size_t>(sched.xcd) * nslots;
+    int* cnt = p.splitk_count + slot0 + lt;
+    int fe, frow0, frow_end, fn0;
+    sched.locate(sched.full + lt, fe, frow0, frow_end, fn0);
+    if (tid == 0) {
+      for (int spin = 0; spin < (1 << 22); ++spin) {
+        if ((__hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 0xff) >= S) break;
+        __builtin_amdgcn_s_sleep(16);
+      }
+    }
+    lds_barrier();
+    const bool xseg = XSEG && fe == p.E;
+    unsigned char* const fC = xseg ? p.xC : p.C;
+    const int64_t fldc = xseg ? p.xldc : p.ldc;
+    const int rm = region / CFG::WN, rn = region - rm * CFG::WN;      // the wave tile's place in the tile
+    const float* first = p.splitk_part + (slot0 + static_cast<size_t>(lt) * S) * TILE;
+#pragma unroll
+    for (int u = 0; u < RPW; ++u) {
+      const int i = wave * RPW + u;                                   // row-subtile of the wave tile
+      const int m = frow0 + rm * CFG::TM + i * 16 + l16;              // this lane's row
+      if (frow0 + rm * CFG::TM + i * 16 >= frow_end) continue;        // (wave-uniform) subtile past the segment
+      const int mc = m < frow_end ? m : frow_end - 1;
+      // what the output decode needs of this row
+      int64_t orow = mc;
+      float rscale = 1.0f;
+      if constexpr (DEC == 1) {
+        orow = p.scatter[mc];
+        rscale = p.row_scale[orow];
+      } else if constexpr (DEC == 2) {
+        if (p.row_scale != nullptr) rscale = p.row_scale[2 * static_cast<int64_t>(mc)];
+      }
+      f32x4_t a[NJ];
+      const float* src = first + ((region * FRAGS + i * NJ) * 64 + lane) * 4;
+      for (int q0 = 0; q0 < S; q0 += 4) {           // four parts per round trip (parts past S - 1: S - 1 again, not added)
+        f32x4_t t[16];
+        const float* pq[4];
+#pragma unroll
+        for (int u4 = 0; u4 < 4; ++u4) pq[u4] = src + static_cast<size_t>(q0 + u4 < S ? q0 + u4 : S - 1) * TILE;
+        load16x16_device_scope(pq[0], pq[1], pq[2], pq[3], t);
+#pragma unroll
+        for (int u4 = 0; u4 < 4; ++u4) {
+          if (q0 + u4 < S) {                         // (wave-uniform)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) a[j] = (q0 + u4 == 0) ? t[u4 * NJ + j] : a[j] + t[u4 * NJ + j];
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int n = fn0 + rn * CFG::TN + j * 16 + 4 * lq;           // four consecutive columns
+        float v[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          v[c] = a[j][c];
+          if (ACT) v[c] = (p.gelu_mode == SCMOE_GELU_TANH) ? gelu_tanh_fast(v[c]) : gelu_erf_fast(v[c]);
+          if (DECODE) v[c] *= rscale;
+        }
+        uint2 o;
+        o.x = cvt_pk_bf16(v[0], v[1]);
+        o.y = cvt_pk_bf16(v[2], v[3]);
+        if (m < frow_end && n < p.N) {
+          if constexpr (DECODE) {
+            if (p.addend != nullptr) {
+              const uint2 ad = *reinterpret_cast<const uint2*>(p.addend + (orow * p.ldadd + n) * 2);
+              o.x = add_bf16x2(o.x, ad.x);
+              o.y = add_bf16x2(o.y, ad.y);
+            }
+          }
+          *reinterpret_cast<uint2*>(fC + (orow * fldc + n) * 2) = o;
+        }
+      }
+    }
+    // the last of a tile's finish items leaves the counter at zero for the next launch
+    lds_barrier();
+    if (tid == 0) {
+      const int old = __hip_atomic_fetch_add(cnt, 0x100, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((old >> 8) == FS - 1) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
 }
 

@@ -134,6 +134,35 @@ __device__ __forceinline__ void load4x16_device_scope(const float* p, f32x4_t& a
       : "memory");
 }
 
+// Sixteen such loads in flight at once: four pieces 1 KiB apart from each of four bases.  (The
+// reader of split-K partial sums has nothing to overlap a round trip to memory with: what
+// counts is how few round trips it makes.)
+__device__ __forceinline__ void load16x16_device_scope(const float* p0, const float* p1, const float* p2,
+                                                       const float* p3, f32x4_t (&t)[16]) {
+  asm volatile(
+      "global_load_dwordx4 %0, %16, off sc1\n\t"
+      "global_load_dwordx4 %1, %16, off offset:1024 sc1\n\t"
+      "global_load_dwordx4 %2, %16, off offset:2048 sc1\n\t"
+      "global_load_dwordx4 %3, %16, off offset:3072 sc1\n\t"
+      "global_load_dwordx4 %4, %17, off sc1\n\t"
+      "global_load_dwordx4 %5, %17, off offset:1024 sc1\n\t"
+      "global_load_dwordx4 %6, %17, off offset:2048 sc1\n\t"
+      "global_load_dwordx4 %7, %17, off offset:3072 sc1\n\t"
+      "global_load_dwordx4 %8, %18, off sc1\n\t"
+      "global_load_dwordx4 %9, %18, off offset:1024 sc1\n\t"
+      "global_load_dwordx4 %10, %18, off offset:2048 sc1\n\t"
+      "global_load_dwordx4 %11, %18, off offset:3072 sc1\n\t"
+      "global_load_dwordx4 %12, %19, off sc1\n\t"
+      "global_load_dwordx4 %13, %19, off offset:1024 sc1\n\t"
+      "global_load_dwordx4 %14, %19, off offset:2048 sc1\n\t"
+      "global_load_dwordx4 %15, %19, off offset:3072 sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]), "=&v"(t[7]),
+        "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11]), "=&v"(t[12]), "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15])
+      : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+      : "memory");
+}
+
 // f(integral_constant<int, I>) for I = B .. N-1, unrolled at compile time.
 template <int B, int N, class F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -172,14 +201,18 @@ struct TileSchedule {
                                   // range; of the other range rr tiles out of the dealt chunks,
                                   // then tiles from b0 on of the undealt rest
   static constexpr int RR = 32;
-  // Work items of this XCD: its `full` tiles that fill whole rounds of nslots workgroups, then
-  // the `rem` tiles of the last round, each cut along K into S parts so that the round keeps
-  // (nearly) all workgroups busy.  Item it < full is local tile it; item full + w is part
-  // w % S of local tile full + w / S.  A workgroup takes items slot, slot + nslots, ...
-  int full, rem, S, nitems, xcd;
+  // Work items of this XCD.  Its `full` tiles fill whole rounds of nslots workgroups; the `rem`
+  // tiles of the last, partly filled round are each cut along K into S parts (S > 1 only with
+  // scratch for the partial sums), so that the round keeps (nearly) all workgroups busy.
+  // Item order: first the rem * S parts (part w % S of local tile full + w / S), then the full
+  // tiles (local tile = item - parts), then rem * FS finish items, one per FS-th of a cut tile,
+  // which add the parts up and write the result.  A workgroup takes items slot, slot + nslots,
+  // ...: a part is always the first item of its workgroup, a finish item the last, so the
+  // partial sums are long written when they are read (the kernel still checks the arrival count).
+  int full, rem, S, npart, ngemm, nfin, xcd;
   int cur_e = 0, cur_base = 0;    // where the last search through offsets[] ended (see locate)
 
-  __device__ __forceinline__ TileSchedule(const GemmArgs& p, int nk, bool can_split)
+  __device__ __forceinline__ TileSchedule(const GemmArgs& p, int nk, bool can_split, int FS)
       : mt_seg(0), nt(p.nt), E(p.E), xt((p.xrows + BM - 1) / BM), xrows(p.xrows), offsets(p.offsets) {
     for (int q = 0; q < E; ++q) mt_seg += (offsets[q + 1] - offsets[q] + BM - 1) / BM;
     xcd = blockIdx.x & 7;
@@ -205,17 +238,18 @@ struct TileSchedule {
       if (S > nk) S = nk;
       if (S < 1) S = 1;
     }
-    nitems = full + rem * S;
+    npart = S > 1 ? rem * S : 0;
+    ngemm = S > 1 ? npart + full : n;
+    nfin = S > 1 ? rem * FS : 0;
   }
-  // item -> local tile index and part (part < 0: the whole tile)
+  // GEMM item (it < ngemm) -> local tile index and part (part < 0: the whole tile)
   __device__ __forceinline__ void item(int it, int& l, int& part) const {
-    if (it < full || S == 1) {
-      l = it;
-      part = -1;
+    if (it < npart) {
+      l = full + it / S;
+      part = it - (it / S) * S;
     } else {
-      const int w = it - full;
-      l = full + w / S;
-      part = w - (w / S) * S;
+      l = it - npart;
+      part = -1;
     }
   }
   // raster order inside a range of mt row tiles: tile l -> row tile, first column
