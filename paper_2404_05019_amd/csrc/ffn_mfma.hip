@@ -82,7 +82,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
 
   // ---- tile schedule ------------------------------------------------------------------------
   const int nk_all = p.Kd / BK;
-  TileSchedule<BM, BN, ACT ? CFG::GM_FIRST : CFG::GM_SECOND> sched(p, nk_all, p.splitk_part != nullptr, CFG::WAVES);
+  TileSchedule<BM, BN, ACT ? CFG::GM_FIRST : CFG::GM_SECOND> sched(p, nk_all, p.splitk_part != nullptr && p.Kd >= SPLITK_MIN_K, CFG::WAVES);
   const int nslots = sched.nslots;
   int it = blockIdx.x >> 3;                // work item: a tile, one K-part of a tile of the last round, or a finish item
   if (it >= sched.ngemm + sched.nfin) return;
@@ -647,7 +647,7 @@ static int launch_gemm_impl(GemmArgs a, int max_rows, hipStream_t stream) {
   const int resident = (num_cus() / 8) * CFG::WG_PER_CU;       // workgroups one XCD holds at once
   if (slots > resident) {
     slots = resident;
-  } else if (a.splitk_part != nullptr) {
+  } else if (a.splitk_part != nullptr && a.Kd >= SPLITK_MIN_K) {
     // Far fewer tiles than workgroups the chip can hold: launch the workgroups anyway, so
     // that the schedule cuts every tile along K (as many slots as the split-K scratch has room
     // for).  From a quarter of the capacity on it no longer pays (measured: tiles cut in two
