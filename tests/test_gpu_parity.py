@@ -277,19 +277,46 @@ def test_expert_ffn_random_segments(oracle, seed):
         B.scmoe_set_gemm_variant(0)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2])
-def test_expert_ffn_split_k_tail(oracle, variant):
-    """With a workspace the last, partly filled round of tiles is cut along K (here: 3 tiles
-    left on one XCD, 1 on another).  Same bar; identical from run to run; the workspace may
-    hold anything on entry."""
-    B.scmoe_set_gemm_variant(variant)
+def test_expert_ffn_split_k_tail(oracle):
+    """Tiles are cut along K from K = 2048 on, when a workspace is given and the last round of
+    workgroups is partly filled.  Here both GEMMs have K = 2048 and 296 tiles of 256 x 256 (37
+    per XCD on 32 workgroups: 32 whole tiles, then 5 tiles in 6 parts each, added up by finish
+    items at the end of the launch); with 128 x 128 tiles 144 per XCD on 128 workgroups.  Every
+    element compared with the oracle, for every tile configuration; identical from run to run;
+    the workspace may hold anything on entry; and close to the call without a workspace."""
+    E, lens, d, F = 3, [4000, 300, 4700], 2048, 2048
+    rng = np.random.default_rng(4321)
+    K = sum(lens)
+    rows = K + 3
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    x = inputs.quantize(rng.standard_normal((rows, d)), "bf16")
+    W1 = inputs.quantize(0.03 * rng.standard_normal((E, F, d)), "bf16")
+    W2 = inputs.quantize(0.03 * rng.standard_normal((E, d, F)), "bf16")
+    b1 = (0.1 * rng.standard_normal((E, F))).astype(np.float32)
+    b2 = (0.1 * rng.standard_normal((E, d))).astype(np.float32)
+    ref = oracle.expert_ffn(x, offsets, W1, W2, b1, b2)
+    gx, gW1, gW2 = to_dev(x, "bf16"), to_dev(W1, "bf16"), to_dev(W2, "bf16")
+    gb1, gb2, goff = to_dev(b1, "f32"), to_dev(b2, "f32"), torch.from_numpy(offsets).to(DEV)
+
+    def run(workspace, fill):
+        hidden = torch.zeros((rows, B.scmoe_padded_ld(F, B.BF16)), dtype=torch.bfloat16, device=DEV)[:, :F]
+        y = torch.full((rows, d), 7.0, dtype=torch.bfloat16, device=DEV)
+        ws = None
+        if workspace:
+            ws = torch.full((B.scmoe_expert_ffn_workspace_bytes(B.BF16, d, F),), fill, dtype=torch.uint8, device=DEV)
+        B.scmoe_expert_ffn(gx, goff, rows, gW1, gb1, gW2, gb2, hidden, y, workspace=ws)
+        torch.cuda.synchronize()
+        return to_host(y)
+
     try:
-        args = (oracle, 3, [1300, 200, 1500], 256, 1024, "bf16", True, 0)
-        g1, _ = _ffn_case(*args, workspace=True)
-        g2, _ = _ffn_case(*args, workspace=True)
-        g0, ref = _ffn_case(*args, workspace=False)
-        assert np.array_equal(g1, g2)
-        assert relerr(g1, g0) <= 1e-2
+        for variant in (0, 1, 2):
+            B.scmoe_set_gemm_variant(variant)
+            g1, g2, g0 = run(True, 0x7f), run(True, 0xc3), run(False, 0)
+            for g in (g1, g0):
+                assert (g[K:] == 7.0).all()
+                assert_close(g[:K], ref[:K], "bf16")
+            assert np.array_equal(g1, g2)
+            assert relerr(g1, g0) <= 1e-2
     finally:
         B.scmoe_set_gemm_variant(0)
 
@@ -384,6 +411,26 @@ def test_layer_bf16_mfma_path(oracle, k, shared, C_, normalize, cg, res, gelu):
         D = DevLayer(dict(L, W2=np.zeros_like(L["W2"]), b2=np.zeros_like(L["b2"])), "bf16")
         s, _ = run_layer(D, 1, C_, True, normalize)
         assert np.array_equal(y[dropped], s[dropped])
+
+
+@pytest.mark.parametrize("k,shared,C_,cg,res,two_streams", [
+    (1, True, 160, 0, False, False),      # routed second GEMM decodes (scatter, gate weight, add) in finish items
+    (1, True, 150, 2, True, False),       # ... and so does the shared expert's (its coefficient, the residual)
+    (1, True, 100000, 1, False, True),    # two streams
+    (1, False, 150, 0, False, False),     # standard top-1 layer: decode with nothing below
+    (2, True, 300, 0, False, False)])     # two routed items per token: plain second GEMMs, combine kernel
+def test_layer_tiles_cut_along_k(oracle, k, shared, C_, cg, res, two_streams):
+    """A layer whose second GEMMs have K = F = 2048 and only a handful of tiles, so that every
+    tile is cut along K and written by finish items: the fused output decodes (scatter and gate
+    weight of the routed rows, coefficient and residual of the shared expert's rows) in that
+    path.  Every row compared with the oracle."""
+    L = inputs.make_layer(T=700, d=256, F=2048, E=4, dtype="bf16", seed=31 + k + cg, biases=True, cg_rows=cg,
+                          w_scale=0.03)
+    y, r, ref, rr = _layer_case(oracle, L, "bf16", 4, k, C_, shared, 0 if k == 1 else 1, cg, 0, res,
+                                two_streams=two_streams)
+    assert_close(y, ref, "bf16")
+    if C_ < 700:
+        assert (r["dst_row"] < 0).any()
 
 
 def test_scmoe2_two_routed_experts_plus_shared(oracle):
