@@ -316,7 +316,8 @@ def main():
         ffn_ws = None
     ms_ffn = time_region(torch, lambda: B.scmoe_expert_ffn(x_perm, offsets, rows, D.W1, D.b1, D.W2, D.b2, hidden,
                                                            y_perm, workspace=ffn_ws), args.steps, 2)
-    ms_comb = time_region(torch, lambda: B.scmoe_combine(y_perm, dst_row, gw, 1, s_out, None, None, y), n_ops, 3)
+    y_leg = torch.empty_like(y)                    # (y keeps the layer output of the timed steps for the parity check)
+    ms_comb = time_region(torch, lambda: B.scmoe_combine(y_perm, dst_row, gw, 1, s_out, None, None, y_leg), n_ops, 3)
 
     if args.calibrate_copy:
         # plain copy of known size: 1 GiB read + 1 GiB written per launch, far larger than the
