@@ -2,8 +2,10 @@
 //
 // The logits decide an integer (the arg max), so their arithmetic is fixed by the ABI:
 // fp32, one fused multiply-add per input feature in ascending feature order, then one
-// rounded add of the bias.  The kernel keeps that chain intact per (token, expert) and
-// finds its parallelism elsewhere: a workgroup owns 64 tokens, lane = token, and each of
+// rounded add of the bias.  Every kernel here keeps that chain intact per (token, expert) and
+// finds its parallelism elsewhere.  Up to 16 experts the chains run on the matrix cores
+// (gate_mfma_kernel: the fp32 matrix instruction is such a chain, four features at a time).
+// With more experts, gate_kernel: a workgroup owns 64 tokens, lane = token, and each of
 // its eight waves (four for E <= 4) owns a contiguous group of EPL experts, so every lane
 // runs EPL independent FMA chains.  x is staged through LDS in [64 tokens x 256 bytes] tiles
 // (coalesced HBM reads although each lane walks its own row), and so is the matching slab
@@ -15,6 +17,9 @@
 // one W read per 16 features with a DPP row broadcast inside the FMA (same time: LDS traffic
 // is not what bounds the kernel).
 #include "common.hpp"
+#include "mfma_common.hpp"
+
+#include <atomic>
 
 namespace scmoe {
 
@@ -255,6 +260,274 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
   }
 }
 
+// E <= 16: the chains run on the matrix cores.  The fp32
+// matrix instruction v_mfma_f32_16x16x4_f32 adds its four products to the accumulator one
+// after the other in ascending k, each step rounded like a fused multiply-add (checked bit for
+// bit against fmaf chains, subnormal sums and cancellation included), so one instruction
+// advances the 16 x 16 chains of 16 tokens and 16 experts by four features: the same bits as
+// the kernels below at a quarter of a dependent instruction per feature and chain.
+// A wave owns 16 tokens.  Nothing passes through registers on the way in: x rows and W_g are
+// copied global -> LDS directly (so the compiler never waits for a register load, which with
+// such copies in flight would drain all of them), x into a ring of XS stages per wave (a
+// stage: 128 bytes of each of the 16 rows, two copies of 1 KiB), W_g in tiles of GM_KC features
+// into two buffers shared by the workgroup (its natural [feature][expert] order is already
+// the operand order: lane (c, kq) of step s reads expert c of feature 4 s + kq).  Operands are
+// read from LDS half a stage ahead of the matrix instructions that use them.  Waits are
+// explicit: copies complete in issue order, so "all but the newest n" names a stage.
+constexpr int GM_STAGE = 2048;           // bytes per stage: 16 rows x 128 bytes
+constexpr int GM_KC = 256;               // features per W_g tile: 1 KiB per expert column
+constexpr int GM_WBUF = GM_KC * 16 * 4;  // bytes per W_g buffer (E = 16)
+constexpr int GM_LGS = 17;               // row stride of the logit exchange buffer
+
+// LDS reads and waits of the matrix-core gate kernel's main loop, written out (see there).
+// The result register of a read is not valid before an lds_wait that names it.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(SCMOE_LDS_PTR(p)));
+}
+template <int OFF>
+__device__ __forceinline__ void lds_read_b32(uint32_t& r, uint32_t addr) {
+  asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+}
+// a bf16 into the upper half of r (whose lower half stays as it is: zero), i.e. the fp32 value
+template <bool BF16, int OFF>
+__device__ __forceinline__ void lds_read_x(uint32_t& r, uint32_t addr) {
+  if constexpr (BF16) asm volatile("ds_read_u16_d16_hi %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFF));
+  else asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+}
+// byte offset, inside a stage, of the x operand of step S (for the lane's row and feature)
+template <bool BF16>
+constexpr int gm_x_off(int S) { return BF16 ? (S >> 1) * 256 + (S & 1) * 8 : S * 256; }
+// until at most N of the LDS reads issued so far are outstanding; a and b are valid afterwards
+template <int N>
+__device__ __forceinline__ void lds_wait(uint32_t& a, uint32_t& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+
+template <bool BF16, int NW, int XS>
+__global__ __launch_bounds__(64 * NW) void gate_mfma_kernel(
+    const unsigned char* __restrict__ x, int64_t ldx, const float* __restrict__ Wg,
+    const float* __restrict__ bias, int T, int d, int E, int k, int normalize,
+    int32_t* __restrict__ expert_idx, float* __restrict__ gate_w, float* __restrict__ probs) {
+  constexpr int EB = BF16 ? 2 : 4;
+  constexpr int SF = 128 / EB;            // features per stage
+  constexpr int SS = SF / 4;              // steps (matrix instructions) per stage
+  constexpr int HS = SS / 2;              // steps per half stage
+  constexpr int IPT = GM_KC / SF;         // stages per W_g tile
+  constexpr int TOK = 16 * NW;
+  static_assert(XS >= 3 && 2 * (XS - 2) < 64, "ring depth");
+  static_assert(2 * (HS - 1) <= 15, "LDS reads a wait can count");
+  static_assert(TOK * GM_LGS * 4 <= GM_WBUF, "logits fit a W_g buffer");
+  extern __shared__ __attribute__((aligned(1024))) unsigned char gm[];   // [W_g buffer 0][W_g buffer 1][NW rings]
+  __shared__ float row_max[TOK];
+  __shared__ float row_sum[TOK];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c16 = lane & 15, kq = lane >> 4;
+  const int t0 = blockIdx.x * TOK;
+  const int NS = d / 4;                                   // steps in all
+  const int NI = (NS + SS - 1) / SS;                      // stages in all
+  unsigned char* const ring = gm + 2 * GM_WBUF + wave * (XS * GM_STAGE);
+
+  // ---- copies --------------------------------------------------------------------------------
+  // x: lane p of a copy fetches 16 bytes of row p % 16 at 16-byte column p / 16 of the 64 bytes
+  // the copy covers; they land at ring position p.  Columns past the row's end re-read its last
+  // 16 bytes (never consumed), and so do whole stages past the end, which keeps the number of
+  // copies per stage fixed for the waits below.
+  int trow = t0 + wave * 16 + c16;
+  if (trow > T - 1) trow = T - 1;
+  const unsigned char* const xrow = x + static_cast<int64_t>(trow) * ldx * EB;
+  const int row_last = d * EB - 16;
+  auto issue_x = [&](int i, int slot) {
+    unsigned char* dst = ring + slot * GM_STAGE;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      int off = i * 128 + h * 64 + kq * 16;
+      if (off > row_last) off = row_last;
+      __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(xrow + off), SCMOE_LDS_PTR(dst + h * 1024), 16, 0, 0);
+    }
+  };
+  // W_g tile j is the bytes [j * 1024 E, (j + 1) * 1024 E) of the matrix, E copies of 1 KiB dealt
+  // to the waves; the last tile may run past the end and re-reads the last 16 bytes there.
+  const unsigned char* const wg = reinterpret_cast<const unsigned char*>(Wg);
+  const int64_t w_last = static_cast<int64_t>(d) * E * 4 - 16;
+  auto issue_w = [&](int j) {
+    unsigned char* dst = gm + (j & 1) * GM_WBUF;
+    for (int u = wave; u < E; u += NW) {
+      int64_t off = (static_cast<int64_t>(j) * E + u) * 1024 + lane * 16;
+      if (off > w_last) off = w_last;
+      __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(wg + off), SCMOE_LDS_PTR(dst + u * 1024), 16, 0, 0);
+    }
+  };
+  auto wait_vm = [&](auto n_c) {
+    constexpr int n = decltype(n_c)::value;
+    static_assert(n < 64, "vmcnt field");
+    __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | 0x0F70);
+    asm volatile("" ::: "memory");
+  };
+  // copies that may still be on their way when stage i + 1 is needed: those of the XS - 2 stages
+  // after it.  At the end of a W_g tile the next tile must be in as well; it was requested IPT
+  // stages of x ago.
+  using InFlight = std::integral_constant<int, 2 * (XS - 2)>;
+  using InFlightTileEnd = std::integral_constant<int, (XS - 2 < IPT) ? 2 * (XS - 2) : 2 * IPT>;
+
+  // ---- operands ------------------------------------------------------------------------------
+  // x: token c16's 16 bytes of 16-byte column q sit at ring position 16 q + c16; W_g: feature
+  // row f of the tile starts at byte 4 E f.  Lanes past the last expert read expert E - 1 again
+  // (their rows of the product are never looked at).
+  const int xl = c16 * 16 + kq * EB;
+  const int wl = (kq * E + (c16 < E ? c16 : E - 1)) * 4;
+  auto read_half = [&](int i, int slot, int h, uint32_t (&xv)[HS], uint32_t (&wv)[HS]) {
+    const unsigned char* xs = ring + slot * GM_STAGE + xl;
+    const unsigned char* ws = gm + ((i / IPT) & 1) * GM_WBUF + ((i % IPT) * SS + h * HS) * 16 * E + wl;
+#pragma unroll
+    for (int s = 0; s < HS; ++s) {
+      const int S = h * HS + s;
+      if (BF16) xv[s] = static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(xs + (S >> 1) * 256 + (S & 1) * 8)) << 16;
+      else xv[s] = *reinterpret_cast<const uint32_t*>(xs + S * 256);
+      wv[s] = *reinterpret_cast<const uint32_t*>(ws + s * 16 * E);
+    }
+  };
+  f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+  // experts are the rows of the product (first operand), tokens its columns: lane (c16, kq)
+  // ends with token c16 and experts 4 kq .. 4 kq + 3
+  auto chain_half = [&](const uint32_t (&xv)[HS], const uint32_t (&wv)[HS], auto full_c, int steps) {
+#pragma unroll
+    for (int s = 0; s < HS; ++s)
+      if (decltype(full_c)::value || s < steps)
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(wv[s]), __uint_as_float(xv[s]), acc, 0, 0, 0);
+  };
+
+  issue_w(0);
+#pragma unroll
+  for (int i = 0; i < XS - 1; ++i) issue_x(i, i);
+  wait_vm(InFlight{});                                    // W_g tile 0 and stage 0 are in LDS
+  lds_barrier();
+  uint32_t xa[HS], xb[HS], wa[HS], wb[HS];                // operand bits (x already widened to fp32)
+#pragma unroll
+  for (int s = 0; s < HS; ++s) xb[s] = 0u;                // (the 16-bit reads keep the lower half of their register)
+  read_half(0, 0, 0, xa, wa);
+  int slot = 0, slot_free = XS - 1;                       // ring slots of stage i and of stage i - 1
+  int i = 0;
+
+  // Whole W_g tiles: IPT stages in straight-line code.  A dependent matrix instruction issues
+  // only when the one before it has finished, and the wave issues in order, so everything else
+  // (the reads of the operands half a stage ahead, their addresses, the copies) is placed
+  // between the matrix instructions, where it costs nothing, and not in a block in front of them.
+  // The operand reads and their waits are written out here (lds_read_*, lds_wait): with
+  // global -> LDS copies in flight every wait the compiler generates is a wait for everything,
+  // i.e. for the reads issued just before.  LDS reads complete in order: a step's operands were
+  // read one half stage earlier, 2 (HS - 1) reads ago.
+  const int NTF = NS / (IPT * SS);
+  for (int j = 0; j < NTF; ++j) {
+    if ((j + 1) * GM_KC < d) issue_w(j + 1);              // its buffer was released by the last barrier
+    const unsigned char* const wt = gm + (j & 1) * GM_WBUF + wl;
+    const unsigned char* const wt_next = gm + ((j + 1) & 1) * GM_WBUF + wl;
+    static_for<0, IPT>([&](auto q_c) {
+      constexpr int q = decltype(q_c)::value;
+      issue_x(i + XS - 1, slot_free);
+      const uint32_t xs = lds_addr(ring + slot * GM_STAGE + xl);
+      slot_free = slot;
+      slot = (slot + 1 == XS) ? 0 : slot + 1;
+      const uint32_t xs_next = lds_addr(ring + slot * GM_STAGE + xl);
+      const uint32_t w2 = lds_addr(wt + (q * SS + HS) * 16 * E);                           // second half of this stage
+      const uint32_t w1 = lds_addr((q == IPT - 1) ? wt_next : wt + (q + 1) * SS * 16 * E); // first half of the next
+      static_for<0, HS>([&](auto s_c) {
+        constexpr int s = decltype(s_c)::value;
+        lds_wait<2 * (HS - 1)>(xa[s], wa[s]);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(wa[s]), __uint_as_float(xa[s]), acc, 0, 0, 0);
+        lds_read_x<BF16, gm_x_off<BF16>(HS + s)>(xb[s], xs);
+        lds_read_b32<0>(wb[s], w2 + s * 16 * E);
+      });
+      if (q == IPT - 1) {
+        wait_vm(InFlightTileEnd{});                       // stage i + 1 and this wave's share of the next W_g tile are in LDS
+        lds_barrier();                                    // every wave has read its last operands of this tile; all shares of the next are in
+      } else {
+        wait_vm(InFlight{});                              // stage i + 1 is in LDS
+      }
+      static_for<0, HS>([&](auto s_c) {
+        constexpr int s = decltype(s_c)::value;
+        lds_wait<2 * (HS - 1)>(xb[s], wb[s]);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(wb[s]), __uint_as_float(xb[s]), acc, 0, 0, 0);
+        lds_read_x<BF16, gm_x_off<BF16>(s)>(xa[s], xs_next);       // (after the last stage: stale but in-bounds LDS, unused)
+        lds_read_b32<0>(wa[s], w1 + s * 16 * E);
+      });
+      ++i;
+    });
+    // the operands just read are carried into the next round in registers the compiler may
+    // copy: they have to be there before it does
+    static_for<0, HS>([&](auto s_c) { lds_wait<0>(xa[decltype(s_c)::value], wa[decltype(s_c)::value]); });
+  }
+  // The rest of a last, partial tile, stage by stage (the last stage may be short).
+  auto stage = [&](auto full_c) {
+    if (i % IPT == 0 && (i / IPT + 1) * GM_KC < d) issue_w(i / IPT + 1);
+    issue_x(i + XS - 1, slot_free);
+    const int steps = NS - i * SS;                        // (a short last stage: at least 2)
+    read_half(i, slot, 1, xb, wb);
+    __builtin_amdgcn_sched_barrier(0);
+    chain_half(xa, wa, full_c, steps);
+    slot_free = slot;
+    slot = (slot + 1 == XS) ? 0 : slot + 1;
+    if ((i + 1) % IPT == 0 && i + 1 < NI) {
+      wait_vm(InFlightTileEnd{});
+      lds_barrier();
+    } else {
+      wait_vm(InFlight{});
+    }
+    read_half(i + 1, slot, 0, xa, wa);
+    __builtin_amdgcn_sched_barrier(0);                    // or the reads sink below the chain, to just before their use
+    chain_half(xb, wb, full_c, steps - HS);
+    ++i;
+  };
+  const int NF = NS / SS;                                 // whole stages
+  while (i < NF) stage(std::true_type{});
+  if (i < NI) stage(std::false_type{});
+  wait_vm(std::integral_constant<int, 0>{});              // no copy may land after the workgroup has given up its LDS
+  lds_barrier();                                          // W_g buffer 0 is free: reuse it for the logits
+  float* lg = reinterpret_cast<float*>(gm);
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int e = 4 * kq + r;
+    if (e < E) {
+      float v = acc[r];
+      if (bias != nullptr) v = __fadd_rn(v, bias[e]);
+      lg[(wave * 16 + c16) * GM_LGS + e] = v;
+    }
+  }
+  __syncthreads();
+  if (tid < TOK)
+    route_token(lg + tid * GM_LGS, E, k, normalize, t0 + tid < T, t0 + tid, expert_idx, gate_w, row_max[tid], row_sum[tid]);
+  if (probs != nullptr) {
+    __syncthreads();
+    const int ntok = (T - t0 < TOK) ? T - t0 : TOK;
+    for (int c = tid; c < ntok * E; c += 64 * NW) {
+      const int tok = c / E, e = c - tok * E;
+      probs[static_cast<int64_t>(t0) * E + c] = expf(lg[tok * GM_LGS + e] - row_max[tok]) / row_sum[tok];
+    }
+  }
+}
+
+template <bool BF16, int NW, int XS>
+static int launch_gate_mfma(const void* x, int64_t ldx, const float* Wg, const float* bias, int T, int d, int E,
+                            int k, int normalize, int32_t* idx, float* gw, float* probs, hipStream_t stream) {
+  constexpr int LDS = 2 * GM_WBUF + NW * XS * GM_STAGE;
+  static_assert(LDS + 2 * 16 * NW * 4 <= 160 * 1024, "LDS of a compute unit");
+  static std::atomic<bool> attr_set[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+  if (dev < 0 || !attr_set[dev].load(std::memory_order_acquire)) {
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_mfma_kernel<BF16, NW, XS>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (err != hipSuccess) return hip_fail(err);
+    if (dev >= 0) attr_set[dev].store(true, std::memory_order_release);
+  }
+  dim3 grid((T + 16 * NW - 1) / (16 * NW)), block(64 * NW);
+  hipLaunchKernelGGL((gate_mfma_kernel<BF16, NW, XS>), grid, block, LDS, stream, static_cast<const unsigned char*>(x), ldx,
+                     Wg, bias, T, d, E, k, normalize, idx, gw, probs);
+  return launch_status();
+}
+
 // Few tokens (decode steps, small batches: up to one workgroup of this kernel per CU;
 // measured d = 2048, E = 16, bf16: 32 us against 59 us for 512 to 2048 tokens, 36 against 60 at
 // 4096): the kernel above would run few workgroups whose lanes each walk a serial chain over
@@ -436,6 +709,24 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
   if (T == 0) return SCMOE_OK;
   if (!x || !Wg || !idx || !gw) return SCMOE_ERR_NULL;
   if (!view_ok(x, ldx, d, dtype)) return SCMOE_ERR_SHAPE;
+  // Up to 16 experts: the matrix-core kernel, at any number of tokens (measured against the two
+  // kernels below, bf16, d = 2048: E = 16, 8 to 4096 tokens: 23 us against 24-26; 32768 tokens:
+  // 32 against 66 us; E = 4, 8 to 8192 tokens: 18 against 66-69 us).
+  if (E <= 16 && aligned16(Wg)) {
+    // A wave takes 16 tokens.  Up to one wave per SIMD: one workgroup of four waves per CU (fewer
+    // waves per workgroup when that leaves CUs idle); beyond that eight waves.  The x ring is as
+    // deep as the LDS allows: what a CU has in flight bounds the rate of a memory-bound kernel.
+    const int64_t waves = (static_cast<int64_t>(T) + 15) / 16;
+    const bool bf = dtype == SCMOE_BF16;
+#define SCMOE_GATE_MFMA(NW, XS)                                                                                    \
+  return bf ? launch_gate_mfma<true, NW, XS>(x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)      \
+            : launch_gate_mfma<false, NW, XS>(x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)
+    if (waves > 4 * num_cus()) { SCMOE_GATE_MFMA(8, 7); }
+    else if (waves > 2 * num_cus()) { SCMOE_GATE_MFMA(4, 8); }
+    else if (waves > num_cus()) { SCMOE_GATE_MFMA(2, 8); }
+    else { SCMOE_GATE_MFMA(1, 8); }
+#undef SCMOE_GATE_MFMA
+  }
   // experts per wave (four waves per workgroup)
   int epad = 1;
   while (epad < E) epad <<= 1;

@@ -32,7 +32,11 @@ def _i32(n, fill=None):
     (4099, 2048, 16, "bf16", 2, True), (300, 128, 33, "f32", 1, True), (1, 16, 2, "f32", 2, False),
     (1500, 256, 8, "bf16", 3, True), (300, 64, 5, "f32", 4, False), (100, 16, 3, "f32", 3, False),
     (200, 40, 64, "bf16", 4, True),
-    (33000, 64, 16, "bf16", 1, True), (32800, 24, 7, "f32", 2, False), (32768, 40, 30, "bf16", 3, True)])   # two tokens per lane
+    (33000, 64, 16, "bf16", 1, True), (32800, 24, 7, "f32", 2, False), (32768, 40, 30, "bf16", 3, True),   # two tokens per lane
+    # up to 16 experts (the matrix-core kernel): whole tiles of 256 features plus a rest, with one
+    # to eight waves per workgroup, both input types
+    (9000, 584, 16, "bf16", 1, True), (5000, 1288, 12, "f32", 2, True), (40000, 520, 16, "bf16", 1, False),
+    (2100, 768, 9, "f32", 1, False), (20000, 512, 8, "bf16", 2, False), (17, 2048, 16, "bf16", 1, False)])
 @pytest.mark.parametrize("normalize", [0, 1])
 def test_gate_parity(oracle, T, d, E, dtype, k, use_bias, normalize):
     rng = np.random.default_rng(T + d + E)
