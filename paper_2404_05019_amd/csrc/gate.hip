@@ -484,6 +484,71 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_kernel(
   while (i < NF) stage(std::true_type{});
   if (i < NI) stage(std::false_type{});
   wait_vm(std::integral_constant<int, 0>{});              // no copy may land after the workgroup has given up its LDS
+  if (k == 1 && probs == nullptr) {
+    // Top-1 without the probability output is routed in registers: a lane folds its four logits,
+    // then the four lanes of a token (16 lanes apart, in ascending expert order) fold theirs.
+    // Same rule and same operations in the same order as route_token, hence the same bits: the
+    // largest logit wins, the lowest index among equals, a NaN only against another NaN; the
+    // softmax denominator is summed expert after expert, handed from lane to lane.
+    // (written with selects, on copies of the accumulators pinned to vector registers: the
+    // same logic as nested branches on the accumulator tuple came out of the compiler with two
+    // of the four logits overwritten by the first one)
+    float v[4];
+    float bv = 0.0f, mx = -INFINITY;
+    int bi = -1;                                          // (no expert yet)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int e = 4 * kq + r;
+      const bool valid = e < E;
+      float a = acc[r];
+      asm volatile("" : "+v"(a));
+      if (bias != nullptr) a = __fadd_rn(a, bias[valid ? e : 0]);
+      v[r] = a;
+      const bool take = valid && (bi < 0 || a > bv || (bv != bv && a == a));
+      bi = take ? e : bi;
+      bv = take ? a : bv;
+      mx = (valid && a > mx) ? a : mx;
+    }
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+      const float pv = __shfl_xor(bv, off), pm = __shfl_xor(mx, off);
+      const int pi = __shfl_xor(bi, off);
+      if (pi >= 0) {
+        if (bi < 0) { bi = pi; bv = pv; }
+        else {
+          const bool mine_first = bi < pi;
+          const float lo = mine_first ? bv : pv, hi = mine_first ? pv : bv;
+          const int lo_i = mine_first ? bi : pi, hi_i = mine_first ? pi : bi;
+          const bool take_hi = hi > lo || (lo != lo && hi == hi);
+          bv = take_hi ? hi : lo;
+          bi = take_hi ? hi_i : lo_i;
+        }
+      }
+      if (pm > mx) mx = pm;
+    }
+    float w = 1.0f;                                       // normalize: the one selected logit's softmax over itself
+    if (!normalize) {
+      float t[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) t[r] = expf(v[r] - mx);
+      float sum = 0.0f;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float sg = sum;                                   // (meaningful in the lanes that hold group g)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (4 * g + r < E) sg += t[r];
+        sum = __shfl(sg, c16 + 16 * g);
+      }
+      w = expf(bv - mx) / sum;
+    }
+    const int t = t0 + wave * 16 + c16;
+    if (kq == 0 && t < T) {
+      expert_idx[t] = bi;
+      gate_w[t] = w;
+    }
+    return;
+  }
   lds_barrier();                                          // W_g buffer 0 is free: reuse it for the logits
   float* lg = reinterpret_cast<float*>(gm);
 #pragma unroll
