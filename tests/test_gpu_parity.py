@@ -36,7 +36,8 @@ def _i32(n, fill=None):
     # up to 16 experts (the matrix-core kernel): whole tiles of 256 features plus a rest, with one
     # to eight waves per workgroup, both input types
     (9000, 584, 16, "bf16", 1, True), (5000, 1288, 12, "f32", 2, True), (40000, 520, 16, "bf16", 1, False),
-    (2100, 768, 9, "f32", 1, False), (20000, 512, 8, "bf16", 2, False), (17, 2048, 16, "bf16", 1, False)])
+    (2100, 768, 9, "f32", 1, False), (20000, 512, 8, "bf16", 2, False), (17, 2048, 16, "bf16", 1, False),
+    (20000, 520, 16, "f32", 1, True), (9000, 264, 5, "f32", 1, False), (6000, 328, 16, "bf16", 1, True)])
 @pytest.mark.parametrize("normalize", [0, 1])
 def test_gate_parity(oracle, T, d, E, dtype, k, use_bias, normalize):
     rng = np.random.default_rng(T + d + E)
