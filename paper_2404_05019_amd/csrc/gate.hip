@@ -3,9 +3,10 @@
 // The logits decide an integer (the arg max), so their arithmetic is fixed by the ABI:
 // fp32, one fused multiply-add per input feature in ascending feature order, then one
 // rounded add of the bias.  Every kernel here keeps that chain intact per (token, expert) and
-// finds its parallelism elsewhere.  Up to 16 experts the chains run on the matrix cores
-// (gate_mfma_kernel: the fp32 matrix instruction is such a chain, four features at a time).
-// With more experts, gate_kernel: a workgroup owns 64 tokens, lane = token, and each of
+// finds its parallelism elsewhere.  The chains run on the matrix cores (gate_mfma_kernel: the
+// fp32 matrix instruction is such a chain, four features at a time).  The two vector-ALU
+// kernels remain for a W_g that is not 16-byte aligned and for a few tokens with many experts.
+// gate_kernel: a workgroup owns 64 tokens, lane = token, and each of
 // its eight waves (four for E <= 4) owns a contiguous group of EPL experts, so every lane
 // runs EPL independent FMA chains.  x is staged through LDS in [64 tokens x 256 bytes] tiles
 // (coalesced HBM reads although each lane walks its own row), and so is the matching slab
@@ -260,24 +261,24 @@ __global__ __launch_bounds__(64 * NW) void gate_kernel(
   }
 }
 
-// E <= 16: the chains run on the matrix cores.  The fp32
+// The chains on the matrix cores.  The fp32
 // matrix instruction v_mfma_f32_16x16x4_f32 adds its four products to the accumulator one
 // after the other in ascending k, each step rounded like a fused multiply-add (checked bit for
 // bit against fmaf chains, subnormal sums and cancellation included), so one instruction
 // advances the 16 x 16 chains of 16 tokens and 16 experts by four features: the same bits as
-// the kernels below at a quarter of a dependent instruction per feature and chain.
+// the kernels below at a quarter of a dependent instruction per feature and chain.  With more
+// than 16 experts a wave keeps EG = 2 or 4 accumulators, one per group of 16 experts, and
+// every step issues EG independent instructions on the same x operand.
 // A wave owns 16 tokens.  Nothing passes through registers on the way in: x rows and W_g are
 // copied global -> LDS directly (so the compiler never waits for a register load, which with
 // such copies in flight would drain all of them), x into a ring of XS stages per wave (a
-// stage: 128 bytes of each of the 16 rows, two copies of 1 KiB), W_g in tiles of GM_KC features
-// into two buffers shared by the workgroup (its natural [feature][expert] order is already
-// the operand order: lane (c, kq) of step s reads expert c of feature 4 s + kq).  Operands are
-// read from LDS half a stage ahead of the matrix instructions that use them.  Waits are
-// explicit: copies complete in issue order, so "all but the newest n" names a stage.
+// stage: 128 bytes of each of the 16 rows, two copies of 1 KiB), W_g in tiles of 256 / EG
+// features into a ring of buffers shared by the workgroup (its natural [feature][expert] order
+// is already the operand order: lane (c, kq) of step s reads expert c of feature 4 s + kq).
+// Operands are read from LDS a few steps ahead of the matrix instructions that use them.  Waits
+// are explicit: copies complete in issue order, so "all but the newest n" names a stage.
 constexpr int GM_STAGE = 2048;           // bytes per stage: 16 rows x 128 bytes
-constexpr int GM_KC = 256;               // features per W_g tile: 1 KiB per expert column
-constexpr int GM_WBUF = GM_KC * 16 * 4;  // bytes per W_g buffer (E = 16)
-constexpr int GM_LGS = 17;               // row stride of the logit exchange buffer
+constexpr int GM_WBUF = 16 * 1024;       // bytes per W_g buffer: a tile of 256 features of 16 experts, 128 of 32, 64 of 64
 
 // LDS reads and waits of the matrix-core gate kernel's main loop, written out (see there).
 // The result register of a read is not valid before an lds_wait that names it.
@@ -297,27 +298,45 @@ __device__ __forceinline__ void lds_read_x(uint32_t& r, uint32_t addr) {
 // byte offset, inside a stage, of the x operand of step S (for the lane's row and feature)
 template <bool BF16>
 constexpr int gm_x_off(int S) { return BF16 ? (S >> 1) * 256 + (S & 1) * 8 : S * 256; }
-// until at most N of the LDS reads issued so far are outstanding; a and b are valid afterwards
-template <int N>
-__device__ __forceinline__ void lds_wait(uint32_t& a, uint32_t& b) {
-  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+// until at most N of the LDS reads issued so far are outstanding; x and w are valid afterwards
+template <int N, int EG>
+__device__ __forceinline__ void lds_wait(uint32_t& x, uint32_t (&w)[EG]) {
+  static_assert(N >= 0 && N < 15 && (EG == 1 || EG == 2 || EG == 4), "lgkmcnt field");
+  if constexpr (EG == 1) asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(w[0]) : "n"(N));
+  else if constexpr (EG == 2) asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(x), "+v"(w[0]), "+v"(w[1]) : "n"(N));
+  else asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(x), "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]) : "n"(N));
 }
 
-template <bool BF16, int NW, int XS>
+// Shape of the kernel for EG groups of 16 experts (E <= 16 EG) and NW waves per workgroup.
+template <bool BF16, int NW, int EG>
+struct GateMfmaCfg {
+  static constexpr int EB = BF16 ? 2 : 4;
+  static constexpr int SF = 128 / EB;                 // features per stage of x
+  static constexpr int SS = SF / 4;                   // steps (of four features) per stage
+  static constexpr int KC = 256 / EG;                 // features per W_g tile: at most 16 KiB
+  static constexpr int IPT = KC / SF;                 // stages per W_g tile
+  static constexpr int WB = EG == 1 ? 2 : EG == 2 ? 3 : 4;             // W_g buffers: tile j + WB - 1 is requested when tile j begins
+  static constexpr int XS = EG == 1 ? (NW == 8 ? 7 : 8) : EG == 2 ? 6 : 5;   // x ring stages per wave
+  static constexpr int P = EG == 1 ? SS / 2 : EG == 2 ? 4 : 2;         // steps the operand reads run ahead of their use
+  static constexpr int LGS = 16 * EG + 1;             // row stride of the logit exchange buffer
+  static constexpr int TOK = 16 * NW;
+  static constexpr int LDS = WB * GM_WBUF + NW * XS * GM_STAGE;
+  static_assert(IPT >= 1 && SS % P == 0 && P <= SS / 2, "steps per stage and per tile");
+  static_assert((P - 1) * (1 + EG) < 15, "LDS reads a wait can count");
+  static_assert(XS >= 3 && 2 * (XS - 2) < 64, "ring depth");
+  static_assert(TOK * LGS * 4 <= WB * GM_WBUF, "the logits fit the W_g buffers");
+  static_assert(LDS + 2 * TOK * 4 <= 160 * 1024, "LDS of a compute unit");
+};
+
+template <bool BF16, int NW, int EG>
 __global__ __launch_bounds__(64 * NW) void gate_mfma_kernel(
     const unsigned char* __restrict__ x, int64_t ldx, const float* __restrict__ Wg,
     const float* __restrict__ bias, int T, int d, int E, int k, int normalize,
     int32_t* __restrict__ expert_idx, float* __restrict__ gate_w, float* __restrict__ probs) {
-  constexpr int EB = BF16 ? 2 : 4;
-  constexpr int SF = 128 / EB;            // features per stage
-  constexpr int SS = SF / 4;              // steps (matrix instructions) per stage
-  constexpr int HS = SS / 2;              // steps per half stage
-  constexpr int IPT = GM_KC / SF;         // stages per W_g tile
-  constexpr int TOK = 16 * NW;
-  static_assert(XS >= 3 && 2 * (XS - 2) < 64, "ring depth");
-  static_assert(2 * (HS - 1) <= 15, "LDS reads a wait can count");
-  static_assert(TOK * GM_LGS * 4 <= GM_WBUF, "logits fit a W_g buffer");
-  extern __shared__ __attribute__((aligned(1024))) unsigned char gm[];   // [W_g buffer 0][W_g buffer 1][NW rings]
+  using C = GateMfmaCfg<BF16, NW, EG>;
+  constexpr int EB = C::EB, SS = C::SS, KC = C::KC, IPT = C::IPT, WB = C::WB, XS = C::XS, P = C::P;
+  constexpr int TOK = C::TOK, LGS = C::LGS;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char gm[];   // [WB W_g buffers][NW rings]
   __shared__ float row_max[TOK];
   __shared__ float row_sum[TOK];
 
@@ -328,7 +347,7 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_kernel(
   const int t0 = blockIdx.x * TOK;
   const int NS = d / 4;                                   // steps in all
   const int NI = (NS + SS - 1) / SS;                      // stages in all
-  unsigned char* const ring = gm + 2 * GM_WBUF + wave * (XS * GM_STAGE);
+  unsigned char* const ring = gm + WB * GM_WBUF + wave * (XS * GM_STAGE);
 
   // ---- copies --------------------------------------------------------------------------------
   // x: lane p of a copy fetches 16 bytes of row p % 16 at 16-byte column p / 16 of the 64 bytes
@@ -348,14 +367,16 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_kernel(
       __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(xrow + off), SCMOE_LDS_PTR(dst + h * 1024), 16, 0, 0);
     }
   };
-  // W_g tile j is the bytes [j * 1024 E, (j + 1) * 1024 E) of the matrix, E copies of 1 KiB dealt
-  // to the waves; the last tile may run past the end and re-reads the last 16 bytes there.
+  // W_g tile j is the bytes [4 KC E j, 4 KC E (j + 1)) of the matrix (whole rows), copied 1 KiB at
+  // a time by the waves in turn; the last copy of a tile may reach into the next tile, and past
+  // the end of the matrix a copy re-reads its last 16 bytes (never consumed).
   const unsigned char* const wg = reinterpret_cast<const unsigned char*>(Wg);
   const int64_t w_last = static_cast<int64_t>(d) * E * 4 - 16;
-  auto issue_w = [&](int j) {
-    unsigned char* dst = gm + (j & 1) * GM_WBUF;
-    for (int u = wave; u < E; u += NW) {
-      int64_t off = (static_cast<int64_t>(j) * E + u) * 1024 + lane * 16;
+  const int w_copies = (E + EG - 1) / EG;                 // = ceil(4 KC E / 1024)
+  auto issue_w = [&](int j, int buf) {
+    unsigned char* dst = gm + buf * GM_WBUF;
+    for (int u = wave; u < w_copies; u += NW) {
+      int64_t off = static_cast<int64_t>(j) * (4 * KC) * E + u * 1024 + lane * 16;
       if (off > w_last) off = w_last;
       __builtin_amdgcn_global_load_lds(SCMOE_GLB_PTR(wg + off), SCMOE_LDS_PTR(dst + u * 1024), 16, 0, 0);
     }
@@ -366,125 +387,138 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_kernel(
     __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | 0x0F70);
     asm volatile("" ::: "memory");
   };
-  // copies that may still be on their way when stage i + 1 is needed: those of the XS - 2 stages
-  // after it.  At the end of a W_g tile the next tile must be in as well; it was requested IPT
-  // stages of x ago.
+  // Copies that may still be on their way when stage i + 1 is needed: those of the XS - 2 stages
+  // after it.  At the end of a W_g tile the next tile must be in as well; it was requested
+  // (WB - 1) IPT stages of x ago (copies complete in issue order).
   using InFlight = std::integral_constant<int, 2 * (XS - 2)>;
-  using InFlightTileEnd = std::integral_constant<int, (XS - 2 < IPT) ? 2 * (XS - 2) : 2 * IPT>;
+  using InFlightTileEnd = std::integral_constant<int, (XS - 2 < (WB - 1) * IPT) ? 2 * (XS - 2) : 2 * (WB - 1) * IPT>;
 
   // ---- operands ------------------------------------------------------------------------------
   // x: token c16's 16 bytes of 16-byte column q sit at ring position 16 q + c16; W_g: feature
   // row f of the tile starts at byte 4 E f.  Lanes past the last expert read expert E - 1 again
   // (their rows of the product are never looked at).
   const int xl = c16 * 16 + kq * EB;
-  const int wl = (kq * E + (c16 < E ? c16 : E - 1)) * 4;
-  auto read_half = [&](int i, int slot, int h, uint32_t (&xv)[HS], uint32_t (&wv)[HS]) {
-    const unsigned char* xs = ring + slot * GM_STAGE + xl;
-    const unsigned char* ws = gm + ((i / IPT) & 1) * GM_WBUF + ((i % IPT) * SS + h * HS) * 16 * E + wl;
+  int wl[EG];
 #pragma unroll
-    for (int s = 0; s < HS; ++s) {
-      const int S = h * HS + s;
-      if (BF16) xv[s] = static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(xs + (S >> 1) * 256 + (S & 1) * 8)) << 16;
-      else xv[s] = *reinterpret_cast<const uint32_t*>(xs + S * 256);
-      wv[s] = *reinterpret_cast<const uint32_t*>(ws + s * 16 * E);
-    }
-  };
-  f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int g = 0; g < EG; ++g) wl[g] = (kq * E + (16 * g + c16 < E ? 16 * g + c16 : E - 1)) * 4;
+  // Operand registers hold what the matrix instruction takes: fp32 bits (a bf16 in the upper half).
+  // P steps are in registers or on their way at any time: step s uses slot s % P.
+  uint32_t xr[P], wr[P][EG];
+  f32x4_t acc[EG];
+#pragma unroll
+  for (int g = 0; g < EG; ++g) acc[g] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
   // experts are the rows of the product (first operand), tokens its columns: lane (c16, kq)
-  // ends with token c16 and experts 4 kq .. 4 kq + 3
-  auto chain_half = [&](const uint32_t (&xv)[HS], const uint32_t (&wv)[HS], auto full_c, int steps) {
+  // ends with token c16 and experts 16 g + 4 kq .. 16 g + 4 kq + 3 of every group g
+  auto chain_step = [&](int slot_r) {
 #pragma unroll
-    for (int s = 0; s < HS; ++s)
-      if (decltype(full_c)::value || s < steps)
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(wv[s]), __uint_as_float(xv[s]), acc, 0, 0, 0);
+    for (int g = 0; g < EG; ++g)
+      acc[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(wr[slot_r][g]), __uint_as_float(xr[slot_r]), acc[g], 0, 0, 0);
+  };
+  // step S of the stage at xs, whose W_g rows start at wrow (plain reads: the compiler waits for them)
+  auto read_step = [&](int slot_r, const unsigned char* xs, const unsigned char* wrow, int S) {
+    if (BF16) xr[slot_r] = static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(xs + gm_x_off<BF16>(S))) << 16;
+    else xr[slot_r] = *reinterpret_cast<const uint32_t*>(xs + gm_x_off<BF16>(S));
+#pragma unroll
+    for (int g = 0; g < EG; ++g) wr[slot_r][g] = *reinterpret_cast<const uint32_t*>(wrow + wl[g]);
   };
 
-  issue_w(0);
+#pragma unroll
+  for (int j = 0; j < WB - 1; ++j)
+    if (j * KC < d) issue_w(j, j);
 #pragma unroll
   for (int i = 0; i < XS - 1; ++i) issue_x(i, i);
-  wait_vm(InFlight{});                                    // W_g tile 0 and stage 0 are in LDS
+  wait_vm(InFlight{});                                    // the first W_g tiles and stage 0 are in LDS
   lds_barrier();
-  uint32_t xa[HS], xb[HS], wa[HS], wb[HS];                // operand bits (x already widened to fp32)
 #pragma unroll
-  for (int s = 0; s < HS; ++s) xb[s] = 0u;                // (the 16-bit reads keep the lower half of their register)
-  read_half(0, 0, 0, xa, wa);
+  for (int s = 0; s < P; ++s) read_step(s, ring + xl, gm + s * 16 * E, s);
   int slot = 0, slot_free = XS - 1;                       // ring slots of stage i and of stage i - 1
+  int wbuf = 0, wbuf_free = WB - 1;                       // buffers of W_g tile j and of tile j - 1
   int i = 0;
+  auto next_slot = [&]() {
+    slot_free = slot;
+    slot = (slot + 1 == XS) ? 0 : slot + 1;
+  };
+  auto next_wbuf = [&]() {
+    wbuf_free = wbuf;
+    wbuf = (wbuf + 1 == WB) ? 0 : wbuf + 1;
+  };
 
   // Whole W_g tiles: IPT stages in straight-line code.  A dependent matrix instruction issues
   // only when the one before it has finished, and the wave issues in order, so everything else
-  // (the reads of the operands half a stage ahead, their addresses, the copies) is placed
-  // between the matrix instructions, where it costs nothing, and not in a block in front of them.
+  // (the reads of the operands P steps ahead, their addresses, the copies) is placed between
+  // the matrix instructions, where it costs nothing, and not in a block in front of them.
   // The operand reads and their waits are written out here (lds_read_*, lds_wait): with
   // global -> LDS copies in flight every wait the compiler generates is a wait for everything,
   // i.e. for the reads issued just before.  LDS reads complete in order: a step's operands were
-  // read one half stage earlier, 2 (HS - 1) reads ago.
+  // read P steps earlier, (P - 1) (1 + EG) reads ago.
   const int NTF = NS / (IPT * SS);
   for (int j = 0; j < NTF; ++j) {
-    if ((j + 1) * GM_KC < d) issue_w(j + 1);              // its buffer was released by the last barrier
-    const unsigned char* const wt = gm + (j & 1) * GM_WBUF + wl;
-    const unsigned char* const wt_next = gm + ((j + 1) & 1) * GM_WBUF + wl;
+    if ((j + WB - 1) * KC < d) issue_w(j + WB - 1, wbuf_free);   // that buffer was released by the last barrier
+    const unsigned char* const wt = gm + wbuf * GM_WBUF;
+    next_wbuf();
+    const unsigned char* const wt_next = gm + wbuf * GM_WBUF;
     static_for<0, IPT>([&](auto q_c) {
       constexpr int q = decltype(q_c)::value;
       issue_x(i + XS - 1, slot_free);
       const uint32_t xs = lds_addr(ring + slot * GM_STAGE + xl);
-      slot_free = slot;
-      slot = (slot + 1 == XS) ? 0 : slot + 1;
+      next_slot();
       const uint32_t xs_next = lds_addr(ring + slot * GM_STAGE + xl);
-      const uint32_t w2 = lds_addr(wt + (q * SS + HS) * 16 * E);                           // second half of this stage
-      const uint32_t w1 = lds_addr((q == IPT - 1) ? wt_next : wt + (q + 1) * SS * 16 * E); // first half of the next
-      static_for<0, HS>([&](auto s_c) {
-        constexpr int s = decltype(s_c)::value;
-        lds_wait<2 * (HS - 1)>(xa[s], wa[s]);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(wa[s]), __uint_as_float(xa[s]), acc, 0, 0, 0);
-        lds_read_x<BF16, gm_x_off<BF16>(HS + s)>(xb[s], xs);
-        lds_read_b32<0>(wb[s], w2 + s * 16 * E);
-      });
-      if (q == IPT - 1) {
-        wait_vm(InFlightTileEnd{});                       // stage i + 1 and this wave's share of the next W_g tile are in LDS
-        lds_barrier();                                    // every wave has read its last operands of this tile; all shares of the next are in
-      } else {
-        wait_vm(InFlight{});                              // stage i + 1 is in LDS
-      }
-      static_for<0, HS>([&](auto s_c) {
-        constexpr int s = decltype(s_c)::value;
-        lds_wait<2 * (HS - 1)>(xb[s], wb[s]);
-        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(wb[s]), __uint_as_float(xb[s]), acc, 0, 0, 0);
-        lds_read_x<BF16, gm_x_off<BF16>(s)>(xa[s], xs_next);       // (after the last stage: stale but in-bounds LDS, unused)
-        lds_read_b32<0>(wa[s], w1 + s * 16 * E);
+      static_for<0, SS>([&](auto s_c) {
+        constexpr int s = decltype(s_c)::value, s2 = s + P;
+        if constexpr (s == SS - P) {                      // the reads of the next stage begin with this step
+          if (q == IPT - 1) {
+            wait_vm(InFlightTileEnd{});                   // stage i + 1 and this wave's share of the next W_g tile are in LDS
+            lds_barrier();                                // every wave has read its last operands of this tile; all shares of the next are in
+          } else {
+            wait_vm(InFlight{});                          // stage i + 1 is in LDS
+          }
+        }
+        lds_wait<(P - 1) * (1 + EG)>(xr[s % P], wr[s % P]);
+        chain_step(s % P);
+        // (after the last stage: stale but in-bounds LDS, unused)
+        const uint32_t xa = s2 < SS ? xs : xs_next;
+        const unsigned char* const wrow = s2 < SS ? wt + (q * SS + s2) * 16 * E
+                                        : q == IPT - 1 ? wt_next + (s2 - SS) * 16 * E : wt + ((q + 1) * SS + s2 - SS) * 16 * E;
+        lds_read_x<BF16, gm_x_off<BF16>(s2 % SS)>(xr[s % P], xa);
+#pragma unroll
+        for (int g = 0; g < EG; ++g) lds_read_b32<0>(wr[s % P][g], lds_addr(wrow + wl[g]));
       });
       ++i;
     });
     // the operands just read are carried into the next round in registers the compiler may
     // copy: they have to be there before it does
-    static_for<0, HS>([&](auto s_c) { lds_wait<0>(xa[decltype(s_c)::value], wa[decltype(s_c)::value]); });
+    static_for<0, P>([&](auto s_c) { lds_wait<0>(xr[decltype(s_c)::value], wr[decltype(s_c)::value]); });
   }
-  // The rest of a last, partial tile, stage by stage (the last stage may be short).
-  auto stage = [&](auto full_c) {
-    if (i % IPT == 0 && (i / IPT + 1) * GM_KC < d) issue_w(i / IPT + 1);
+  // The rest of a last, partial tile, stage by stage, with plain reads (the last stage may be short).
+  while (i < NI) {
+    const int q = i % IPT;
+    if (q == 0 && (i / IPT + WB - 1) * KC < d) issue_w(i / IPT + WB - 1, wbuf_free);
     issue_x(i + XS - 1, slot_free);
-    const int steps = NS - i * SS;                        // (a short last stage: at least 2)
-    read_half(i, slot, 1, xb, wb);
-    __builtin_amdgcn_sched_barrier(0);
-    chain_half(xa, wa, full_c, steps);
-    slot_free = slot;
-    slot = (slot + 1 == XS) ? 0 : slot + 1;
-    if ((i + 1) % IPT == 0 && i + 1 < NI) {
-      wait_vm(InFlightTileEnd{});
-      lds_barrier();
-    } else {
-      wait_vm(InFlight{});
-    }
-    read_half(i + 1, slot, 0, xa, wa);
-    __builtin_amdgcn_sched_barrier(0);                    // or the reads sink below the chain, to just before their use
-    chain_half(xb, wb, full_c, steps - HS);
+    const int steps = NS - i * SS;                        // at least 2; SS or more unless this is the last stage
+    const unsigned char* const xs = ring + slot * GM_STAGE + xl;
+    next_slot();
+    const unsigned char* const xs_next = ring + slot * GM_STAGE + xl;
+    const unsigned char* const wt = gm + wbuf * GM_WBUF;
+    const unsigned char* const wt_next = gm + (wbuf + 1 == WB ? 0 : wbuf + 1) * GM_WBUF;
+    if (q == IPT - 1) next_wbuf();
+    static_for<0, SS>([&](auto s_c) {
+      constexpr int s = decltype(s_c)::value, s2 = s + P;
+      if constexpr (s == SS - P) {
+        if (q == IPT - 1 && i + 1 < NI) {
+          wait_vm(InFlightTileEnd{});
+          lds_barrier();
+        } else {
+          wait_vm(InFlight{});
+        }
+      }
+      if (s < steps) chain_step(s % P);
+      if (s2 < SS) read_step(s % P, xs, wt + (q * SS + s2) * 16 * E, s2);
+      else read_step(s % P, xs_next, q == IPT - 1 ? wt_next + (s2 - SS) * 16 * E : wt + ((q + 1) * SS + s2 - SS) * 16 * E, s2 - SS);
+    });
     ++i;
-  };
-  const int NF = NS / SS;                                 // whole stages
-  while (i < NF) stage(std::true_type{});
-  if (i < NI) stage(std::false_type{});
+  }
   wait_vm(std::integral_constant<int, 0>{});              // no copy may land after the workgroup has given up its LDS
-  if (k == 1 && probs == nullptr) {
+  if (EG == 1 && k == 1 && probs == nullptr) {
     // Top-1 without the probability output is routed in registers: a lane folds its four logits,
     // then the four lanes of a token (16 lanes apart, in ascending expert order) fold theirs.
     // Same rule and same operations in the same order as route_token, hence the same bits: the
@@ -500,7 +534,7 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_kernel(
     for (int r = 0; r < 4; ++r) {
       const int e = 4 * kq + r;
       const bool valid = e < E;
-      float a = acc[r];
+      float a = acc[0][r];
       asm volatile("" : "+v"(a));
       if (bias != nullptr) a = __fadd_rn(a, bias[valid ? e : 0]);
       v[r] = a;
@@ -549,46 +583,48 @@ __global__ __launch_bounds__(64 * NW) void gate_mfma_kernel(
     }
     return;
   }
-  lds_barrier();                                          // W_g buffer 0 is free: reuse it for the logits
+  lds_barrier();                                          // the W_g buffers are free: reuse them for the logits
   float* lg = reinterpret_cast<float*>(gm);
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int e = 4 * kq + r;
-    if (e < E) {
-      float v = acc[r];
-      if (bias != nullptr) v = __fadd_rn(v, bias[e]);
-      lg[(wave * 16 + c16) * GM_LGS + e] = v;
+  for (int g = 0; g < EG; ++g) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int e = 16 * g + 4 * kq + r;
+      if (e < E) {
+        float v = acc[g][r];
+        if (bias != nullptr) v = __fadd_rn(v, bias[e]);
+        lg[(wave * 16 + c16) * LGS + e] = v;
+      }
     }
   }
   __syncthreads();
   if (tid < TOK)
-    route_token(lg + tid * GM_LGS, E, k, normalize, t0 + tid < T, t0 + tid, expert_idx, gate_w, row_max[tid], row_sum[tid]);
+    route_token(lg + tid * LGS, E, k, normalize, t0 + tid < T, t0 + tid, expert_idx, gate_w, row_max[tid], row_sum[tid]);
   if (probs != nullptr) {
     __syncthreads();
     const int ntok = (T - t0 < TOK) ? T - t0 : TOK;
     for (int c = tid; c < ntok * E; c += 64 * NW) {
       const int tok = c / E, e = c - tok * E;
-      probs[static_cast<int64_t>(t0) * E + c] = expf(lg[tok * GM_LGS + e] - row_max[tok]) / row_sum[tok];
+      probs[static_cast<int64_t>(t0) * E + c] = expf(lg[tok * LGS + e] - row_max[tok]) / row_sum[tok];
     }
   }
 }
 
-template <bool BF16, int NW, int XS>
+template <bool BF16, int NW, int EG>
 static int launch_gate_mfma(const void* x, int64_t ldx, const float* Wg, const float* bias, int T, int d, int E,
                             int k, int normalize, int32_t* idx, float* gw, float* probs, hipStream_t stream) {
-  constexpr int LDS = 2 * GM_WBUF + NW * XS * GM_STAGE;
-  static_assert(LDS + 2 * 16 * NW * 4 <= 160 * 1024, "LDS of a compute unit");
+  constexpr int LDS = GateMfmaCfg<BF16, NW, EG>::LDS;
   static std::atomic<bool> attr_set[64];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
   if (dev < 0 || !attr_set[dev].load(std::memory_order_acquire)) {
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_mfma_kernel<BF16, NW, XS>),
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gate_mfma_kernel<BF16, NW, EG>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (err != hipSuccess) return hip_fail(err);
     if (dev >= 0) attr_set[dev].store(true, std::memory_order_release);
   }
   dim3 grid((T + 16 * NW - 1) / (16 * NW)), block(64 * NW);
-  hipLaunchKernelGGL((gate_mfma_kernel<BF16, NW, XS>), grid, block, LDS, stream, static_cast<const unsigned char*>(x), ldx,
+  hipLaunchKernelGGL((gate_mfma_kernel<BF16, NW, EG>), grid, block, LDS, stream, static_cast<const unsigned char*>(x), ldx,
                      Wg, bias, T, d, E, k, normalize, idx, gw, probs);
   return launch_status();
 }
@@ -774,27 +810,37 @@ int gate_topk(const void* x, int64_t ldx, int dtype, const float* Wg, const floa
   if (T == 0) return SCMOE_OK;
   if (!x || !Wg || !idx || !gw) return SCMOE_ERR_NULL;
   if (!view_ok(x, ldx, d, dtype)) return SCMOE_ERR_SHAPE;
-  // Up to 16 experts: the matrix-core kernel, at any number of tokens (measured against the two
-  // kernels below, bf16, d = 2048: E = 16, 8 to 4096 tokens: 23 us against 24-26; 32768 tokens:
-  // 32 against 66 us; E = 4, 8 to 8192 tokens: 18 against 66-69 us).
-  if (E <= 16 && aligned16(Wg)) {
-    // A wave takes 16 tokens.  Up to one wave per SIMD: one workgroup of four waves per CU (fewer
-    // waves per workgroup when that leaves CUs idle); beyond that eight waves.  The x ring is as
-    // deep as the LDS allows: what a CU has in flight bounds the rate of a memory-bound kernel.
-    const int64_t waves = (static_cast<int64_t>(T) + 15) / 16;
-    const bool bf = dtype == SCMOE_BF16;
-#define SCMOE_GATE_MFMA(NW, XS)                                                                                    \
-  return bf ? launch_gate_mfma<true, NW, XS>(x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)      \
-            : launch_gate_mfma<false, NW, XS>(x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)
-    if (waves > 4 * num_cus()) { SCMOE_GATE_MFMA(8, 7); }
-    else if (waves > 2 * num_cus()) { SCMOE_GATE_MFMA(4, 8); }
-    else if (waves > num_cus()) { SCMOE_GATE_MFMA(2, 8); }
-    else { SCMOE_GATE_MFMA(1, 8); }
-#undef SCMOE_GATE_MFMA
-  }
-  // experts per wave (four waves per workgroup)
+  // The matrix-core kernel, at any number of tokens (measured against the two kernels below,
+  // bf16, d = 2048: E = 16, 8 to 4096 tokens: 23 us against 24-26; 32768 tokens: 32 against 66 us;
+  // E = 4, 8 to 8192 tokens: 18 against 66-69 us).  Its copies of W_g need 16-byte alignment.
   int epad = 1;
   while (epad < E) epad <<= 1;
+  // (a few tokens with more than 16 experts: a wave would walk 2-4 chains per step alone; the
+  // one-lane-per-chain kernel below is 10-20 % faster there: 64 tokens, d = 2048, E = 32: 35
+  // against 43 us, E = 64: 75 against 80)
+  const bool few_many = E > 16 && static_cast<int64_t>(T) * epad <= GATE_SMALL_LANES / 8;
+  if (aligned16(Wg) && !few_many) {
+    // A wave takes 16 tokens.  Up to one wave per SIMD: one workgroup of four waves per CU (fewer
+    // waves per workgroup when that leaves CUs idle); beyond that eight waves.
+    const int64_t waves = (static_cast<int64_t>(T) + 15) / 16;
+    const bool bf = dtype == SCMOE_BF16;
+    const int nw = waves > 4 * num_cus() ? 8 : waves > 2 * num_cus() ? 4 : waves > num_cus() ? 2 : 1;
+#define SCMOE_GATE_MFMA(NW, EG)                                                                                    \
+  return bf ? launch_gate_mfma<true, NW, EG>(x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)      \
+            : launch_gate_mfma<false, NW, EG>(x, ldx, Wg, bias, T, d, E, k, normalize, idx, gw, probs, stream)
+#define SCMOE_GATE_MFMA_NW(EG)                                                                                     \
+  switch (nw) {                                                                                                    \
+    case 8: SCMOE_GATE_MFMA(8, EG);                                                                                \
+    case 4: SCMOE_GATE_MFMA(4, EG);                                                                                \
+    case 2: SCMOE_GATE_MFMA(2, EG);                                                                                \
+    default: SCMOE_GATE_MFMA(1, EG);                                                                               \
+  }
+    if (E <= 16) { SCMOE_GATE_MFMA_NW(1) }
+    else if (E <= 32) { SCMOE_GATE_MFMA_NW(2) }
+    else { SCMOE_GATE_MFMA_NW(4) }
+#undef SCMOE_GATE_MFMA_NW
+#undef SCMOE_GATE_MFMA
+  }
   if (static_cast<int64_t>(T) * epad <= GATE_SMALL_LANES) {
     const int tpw = 256 / epad, eb = elem_bytes(dtype);
     // features per chunk: W chunk <= 32 KiB, x chunk <= 28 KiB (60 KiB of dynamic LDS beside

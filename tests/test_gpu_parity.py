@@ -37,7 +37,11 @@ def _i32(n, fill=None):
     # to eight waves per workgroup, both input types
     (9000, 584, 16, "bf16", 1, True), (5000, 1288, 12, "f32", 2, True), (40000, 520, 16, "bf16", 1, False),
     (2100, 768, 9, "f32", 1, False), (20000, 512, 8, "bf16", 2, False), (17, 2048, 16, "bf16", 1, False),
-    (20000, 520, 16, "f32", 1, True), (9000, 264, 5, "f32", 1, False), (6000, 328, 16, "bf16", 1, True)])
+    (20000, 520, 16, "f32", 1, True), (9000, 264, 5, "f32", 1, False), (6000, 328, 16, "bf16", 1, True),
+    # 17 to 64 experts: two or four accumulators per wave, tiles of 128 or 64 features
+    (3000, 640, 32, "bf16", 1, True), (40000, 264, 24, "f32", 2, False), (9000, 520, 64, "bf16", 1, False),
+    (2000, 1032, 48, "f32", 1, True), (70000, 128, 17, "bf16", 2, False), (20000, 392, 64, "f32", 3, True),
+    (5000, 2048, 64, "bf16", 1, False), (12000, 136, 33, "bf16", 4, True)])
 @pytest.mark.parametrize("normalize", [0, 1])
 def test_gate_parity(oracle, T, d, E, dtype, k, use_bias, normalize):
     rng = np.random.default_rng(T + d + E)
@@ -77,6 +81,26 @@ def test_gate_integer_ties_and_strided_view(oracle):
     B.scmoe_gate_top2(big[:, :d], to_dev(Wg, "f32"), None, gi, gw, None, normalize=1)
     torch.cuda.synchronize()
     assert np.array_equal(gi.cpu().numpy().reshape(T, 2), idx)
+
+
+@pytest.mark.parametrize("T,d,E,dtype", [(40, 264, 16, "bf16"), (3000, 264, 16, "bf16"), (70000, 72, 8, "f32"),
+                                         (600, 136, 40, "bf16"), (40000, 64, 64, "bf16")])
+def test_gate_weights_not_16_byte_aligned(oracle, T, d, E, dtype):
+    """W_g at an address that is a multiple of 4 but not of 16: the matrix-core kernel copies W_g
+    in 16-byte pieces and leaves such calls to the vector-ALU kernels.  Same results."""
+    rng = np.random.default_rng(T + E)
+    x = inputs.quantize(rng.standard_normal((T, d)), dtype)
+    Wg = (0.02 * rng.standard_normal((d, E))).astype(np.float32)
+    idx, w, _ = oracle.gate(x, Wg, None, 2, 0)
+    buf = torch.zeros(d * E + 1, dtype=torch.float32, device=DEV)
+    gW = buf[1:].view(d, E)
+    gW.copy_(torch.from_numpy(Wg))
+    assert gW.data_ptr() % 16 == 4
+    gi, gw = _i32(T * 2), torch.empty(T * 2, dtype=torch.float32, device=DEV)
+    B.scmoe_gate_top2(to_dev(x, dtype), gW, None, gi, gw, None, normalize=0)
+    torch.cuda.synchronize()
+    assert np.array_equal(gi.cpu().numpy().reshape(T, 2), idx)
+    assert np.abs(gw.cpu().numpy().reshape(T, 2).astype(np.float64) - w).max() <= 1e-6
 
 
 def test_gate_nan_rule(oracle):
