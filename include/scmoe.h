@@ -157,7 +157,8 @@ int scmoe_capacity(int32_t T, int32_t E, int32_t k, double cf, int32_t* C);
  *
  * The ascending-i single-FMA chain is part of the contract: it fixes the logits bit for
  * bit and with them the routing.  x: [T, d] with stride ldx, dtype as given (bf16 is
- * widened exactly).  W_g: [d, E] fp32, E <= SCMOE_MAX_EXPERTS.
+ * widened exactly).  W_g: [d, E] fp32, E <= SCMOE_MAX_EXPERTS; any 4-byte aligned address is
+ * accepted, a 16-byte aligned one takes the faster kernel (the results are the same).
  */
 int scmoe_gate_top1(const void* x, int64_t ldx, int32_t dtype, const float* W_g,
                     const float* bias, int32_t T, int32_t d, int32_t E, int32_t normalize,
