@@ -324,6 +324,8 @@ int scmoe_workspace_bytes(const scmoe_desc* desc, size_t* out);
  * combine kernel.  With stream_aux == NULL
  * everything runs in order on stream_main (and, on the bf16 MFMA path, the first GEMMs of the
  * shared and the routed experts share one launch).  The result is ready on stream_main.
+ * (Measured on one MI355X: kernels of a few thousand tokens and more fill the chip and a second
+ * stream gains nothing; up to about 4096 tokens it saves 5-13 % of the call.)
  * desc->k = 1 is ScMoE; desc->k = 2 routes two experts per token on x_prev (ScMoE-2,
  * appendix "more activated experts"); larger k up to SCMOE_MAX_TOPK follows the same rule.
  * With desc->cg_mode != 0 the coefficient gate reads x_cur.
