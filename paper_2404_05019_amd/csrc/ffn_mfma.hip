@@ -401,6 +401,7 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
       const size_t slot0 = static_cast<size_t>(sched.xcd) * nslots;   // this XCD's scratch slots
       // accumulator (i, j) of wave w and lane l sits at float4 index (w * FRAGS + i * NJ + j) * 64 + l
       float* mine = p.splitk_part + (slot0 + cw) * TILE + ((wave * FRAGS) * 64 + lane) * 4;
+      mfma_results_settle();
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll

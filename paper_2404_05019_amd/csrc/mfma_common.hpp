@@ -120,12 +120,22 @@ __device__ __forceinline__ uint32_t add_bf16x2(uint32_t a, uint32_t b) {
   return cvt_pk_bf16(lo, hi);
 }
 
+// A precaution between the last matrix instruction and instructions written out in asm that
+// read its results: the compiler inserts the wait states an MFMA result needs ahead of the
+// instructions it schedules itself, and is not known to do so ahead of these.
+__device__ __forceinline__ void mfma_results_settle() {
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+}
+
 // 16-byte store / loads at device scope (sc1: past the caches that are not shared by the whole
 // device), for data handed from one workgroup to another inside a kernel.  The store is not
 // waited for here (follow it with a vmcnt(0) wait before publishing); the load reads four
 // pieces 1 KiB apart and returns when they have arrived.
 __device__ __forceinline__ void store16_device_scope(float* p, f32x4_t v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+  // (the wait state after it: a store of more than 8 bytes per lane still reads its data
+  // registers when the next instruction issues, and the compiler, which keeps that hazard for
+  // its own stores, does not know that this is one)
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void load4x16_device_scope(const float* p, f32x4_t& a, f32x4_t& b, f32x4_t& c, f32x4_t& d) {
   asm volatile(

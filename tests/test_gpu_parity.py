@@ -265,7 +265,10 @@ def test_expert_ffn_many_tiles(oracle, E, lens, d, F, workspace):
     (8, [0, 65, 0, 0, 16, 33, 0, 14], 128, 320, True, 1, True),
     (64, [5] * 64, 64, 192, False, 0, False),
     (2, [40, 24], 1024, 576, True, 0, False),               # 33-64 rows in all: 64-row blocks, cut along K
-    (1, [50], 256, 2048, True, 1, True)])
+    (1, [50], 256, 2048, True, 1, True),
+    # the widths of a decode step of the large workload: many parts along K, whose last one to
+    # arrive adds them up
+    (1, [33], 2048, 8192, True, 0, False), (1, [64], 2048, 8192, False, 0, False), (2, [20, 12], 2048, 4096, True, 0, False)])
 @pytest.mark.parametrize("workspace", [False, True])
 def test_expert_ffn_few_rows(oracle, E, lens, d, F, biases, gelu_mode, pad, workspace):
     """Calls of at most 64 rows, or of segments averaging at most 16 rows (decode steps), take
