@@ -600,11 +600,12 @@ using CfgB = TileCfg<256, 256, 32, 2, 4, 4>;   // 8 waves, 4 stages, 128 KiB LDS
 #define SCMOE_SMALL_TILES 4      // in quarters of the CU count
 #endif
 using CfgS = TileCfg<128, 128, 32, 1, 2, 2>;   // 2 waves, 40 KiB LDS, four workgroups per CU: small problems
+using CfgT = TileCfg<128, 128, 64, 1, 2, 3>;   // 2 waves, 100 KiB LDS, one workgroup per CU: fewer 128 x 128 tiles than CUs
 
 // Tile configuration in use: 0 unless scmoe_set_gemm_variant has set another.  The one piece of
 // process-wide state of the library: an atomic, read once per launch.
 static std::atomic<int> g_variant{0};
-constexpr int NUM_VARIANTS = 3;
+constexpr int NUM_VARIANTS = 4;
 
 static int gemm_variant() { return g_variant.load(std::memory_order_relaxed); }
 
@@ -694,13 +695,24 @@ static int launch_variant(const GemmArgs& a, int max_rows, int64_t a_rows, hipSt
   switch (gemm_variant()) {
     case 1: return launch_gemm<CfgB, ACT>(a, max_rows, a_rows, stream);
     case 2: return launch_gemm<CfgS, ACT>(a, max_rows, a_rows, stream);
+    case 3: return launch_gemm<CfgT, ACT>(a, max_rows, a_rows, stream);
     default: break;
   }
   // Variant 0 picks by size: a problem whose 256 x 256 tiles would not give every CU one is
   // cut into 128 x 128 tiles instead (four small workgroups per CU).
   const int64_t tiles = (static_cast<int64_t>(max_rows) / CfgA::BM + a.E + (a.xrows + CfgA::BM - 1) / CfgA::BM) *
                         ((a.N + CfgA::BN - 1) / CfgA::BN);
-  if (tiles < SCMOE_SMALL_TILES * num_cus() / 4) return launch_gemm<CfgS, ACT>(a, max_rows, a_rows, stream);
+  if (tiles < SCMOE_SMALL_TILES * num_cus() / 4) {
+    // Not even one 128 x 128 tile per CU: every workgroup is alone on its CU and walks all of K
+    // with two waves, so the k-tiles are 64 deep (half as many barriers and waits for the same
+    // arithmetic; measured on the small workload's second GEMMs, 192 tiles: 27.8 -> 24.1 us and
+    // 32.7 -> 28.1 us; with more tiles than CUs the 32-deep form is faster, the first GEMM there
+    // by a factor of two).
+    const int64_t tiles_s = ((static_cast<int64_t>(max_rows) + CfgS::BM - 1) / CfgS::BM + a.E +
+                             (a.xrows + CfgS::BM - 1) / CfgS::BM) * ((a.N + CfgS::BN - 1) / CfgS::BN);
+    if (tiles_s <= num_cus()) return launch_gemm<CfgT, ACT>(a, max_rows, a_rows, stream);
+    return launch_gemm<CfgS, ACT>(a, max_rows, a_rows, stream);
+  }
   return launch_gemm<CfgA, ACT>(a, max_rows, a_rows, stream);
 }
 

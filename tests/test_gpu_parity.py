@@ -300,7 +300,7 @@ def test_expert_ffn_random_segments(oracle, seed):
     E = int(rng.integers(1, 11))
     lens = [int(v) for v in rng.integers(0, 701, E) * (rng.random(E) > 0.2)]
     d, F = 64 * int(rng.integers(1, 9)), 64 * int(rng.integers(1, 13))
-    B.scmoe_set_gemm_variant(seed % 3)
+    B.scmoe_set_gemm_variant(seed % 4)
     try:
         _ffn_case(oracle, E, lens, d, F, "bf16", bool(rng.integers(0, 2)), int(rng.integers(0, 2)),
                   extra_rows=int(rng.integers(0, 9)), pad=bool(rng.integers(0, 2)),
@@ -341,7 +341,7 @@ def test_expert_ffn_split_k_tail(oracle):
         return to_host(y)
 
     try:
-        for variant in (0, 1, 2):
+        for variant in (0, 1, 2, 3):
             B.scmoe_set_gemm_variant(variant)
             g1, g2, g0 = run(True, 0x7f), run(True, 0xc3), run(False, 0)
             for g in (g1, g0):
@@ -353,7 +353,7 @@ def test_expert_ffn_split_k_tail(oracle):
         B.scmoe_set_gemm_variant(0)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 def test_expert_ffn_tile_variants(oracle, variant):
     """Every tile configuration of the MFMA grouped GEMM meets the same bar."""
     B.scmoe_set_gemm_variant(variant)
