@@ -124,9 +124,9 @@ int scmoe_last_hip_error(void);
  * tests; a call that races with a change of the knob uses the old or the new value.
  * 0 (default) = chosen per launch: 256x256x64 tiles,
  * 8 waves, 2 LDS stages, or 128x128 tiles, 2 waves, when the larger tiles would not give
- * every compute unit one (128x128x32, or 128x128x64 with 3 stages when even those are fewer
- * than the compute units); 1 = always 256x256x32, 8 waves, 4 stages; 2 = always 128x128x32;
- * 3 = always 128x128x64.
+ * every compute unit one (128x128x32, or 128x128x64 with 4 waves and 3 stages when even those
+ * are fewer than the compute units); 1 = always 256x256x32, 8 waves, 4 stages; 2 = always
+ * 128x128x32; 3 = always 128x128x64.
  * Results agree to bf16 rounding of the same fp32 sums; only speed differs.  Other values
  * give SCMOE_ERR_ARG. */
 int scmoe_set_gemm_variant(int32_t variant);

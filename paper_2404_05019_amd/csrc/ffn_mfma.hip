@@ -55,7 +55,7 @@ struct TileCfg {
   // d = 2048), and groups of 4 x 8 tiles coincide with the chunks the XCDs are dealt.
   static constexpr int GM_FIRST = 6, GM_SECOND = 4;
   static_assert(BM % (RPL * WAVES) == 0 && BN % (RPL * WAVES) == 0, "loads must divide evenly");
-  static_assert(TM == 128 && TN == 64 && (BK == 32 || BK == 64) && NS >= 2 && NS <= 4, "tile shape");
+  static_assert((TM == 128 || TM == 64) && TN == 64 && (BK == 32 || BK == 64) && NS >= 2 && NS <= 4, "tile shape");
   static_assert(LDS_BYTES * WG_PER_CU <= 160 * 1024 && WG_PER_CU >= 1, "LDS budget");
 };
 
@@ -369,13 +369,13 @@ __global__ __launch_bounds__(CFG::THREADS, CFG::WG_PER_CU * CFG::WAVES / 4) void
     auto decode_loads = [&]() {
       if constexpr (DECODE) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < CFG::TM / 64; ++q) {
           int r = crow0 + wave_m * CFG::TM + q * 64 + lane;
           if (r > crow_end - 1) r = crow_end - 1;      // rows past the segment: its last row (never stored)
           dtok[q] = (DEC == 1) ? p.scatter[r] : r;
         }
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < CFG::TM / 64; ++q) {
           if (DEC == 1) dscale[q] = p.row_scale[dtok[q]];
           else dscale[q] = p.row_scale ? p.row_scale[2 * static_cast<int64_t>(dtok[q])] : 1.0f;
         }
@@ -600,7 +600,7 @@ using CfgB = TileCfg<256, 256, 32, 2, 4, 4>;   // 8 waves, 4 stages, 128 KiB LDS
 #define SCMOE_SMALL_TILES 4      // in quarters of the CU count
 #endif
 using CfgS = TileCfg<128, 128, 32, 1, 2, 2>;   // 2 waves, 40 KiB LDS, four workgroups per CU: small problems
-using CfgT = TileCfg<128, 128, 64, 1, 2, 3>;   // 2 waves, 100 KiB LDS, one workgroup per CU: fewer 128 x 128 tiles than CUs
+using CfgT = TileCfg<128, 128, 64, 2, 2, 3>;   // 4 waves of 64 x 64, 104 KiB LDS, one workgroup per CU: fewer 128 x 128 tiles than CUs
 
 // Tile configuration in use: 0 unless scmoe_set_gemm_variant has set another.  The one piece of
 // process-wide state of the library: an atomic, read once per launch.
@@ -703,11 +703,12 @@ static int launch_variant(const GemmArgs& a, int max_rows, int64_t a_rows, hipSt
   const int64_t tiles = (static_cast<int64_t>(max_rows) / CfgA::BM + a.E + (a.xrows + CfgA::BM - 1) / CfgA::BM) *
                         ((a.N + CfgA::BN - 1) / CfgA::BN);
   if (tiles < SCMOE_SMALL_TILES * num_cus() / 4) {
-    // Not even one 128 x 128 tile per CU: every workgroup is alone on its CU and walks all of K
-    // with two waves, so the k-tiles are 64 deep (half as many barriers and waits for the same
-    // arithmetic; measured on the small workload's second GEMMs, 192 tiles: 27.8 -> 24.1 us and
-    // 32.7 -> 28.1 us; with more tiles than CUs the 32-deep form is faster, the first GEMM there
-    // by a factor of two).
+    // Not even one 128 x 128 tile per CU: every workgroup is alone on its CU and walks all of K,
+    // and what the launch lacks is waves.  Then a tile gets four waves of 64 x 64 (one per
+    // SIMD) and k-tiles 64 deep in three LDS stages (half as many barriers and waits for the
+    // same arithmetic).  Measured on the small workload's second GEMMs (192 tiles): 27.8 -> 18.4 us
+    // and 32.7 -> 21.0 us (two waves with 64-deep k-tiles: 24.1 and 28.1).  With more tiles than
+    // CUs the two-wave 32-deep form is faster, the first GEMM there by a factor of two.
     const int64_t tiles_s = ((static_cast<int64_t>(max_rows) + CfgS::BM - 1) / CfgS::BM + a.E +
                              (a.xrows + CfgS::BM - 1) / CfgS::BM) * ((a.N + CfgS::BN - 1) / CfgS::BN);
     if (tiles_s <= num_cus()) return launch_gemm<CfgT, ACT>(a, max_rows, a_rows, stream);
