@@ -67,6 +67,37 @@ def test_gate_parity(oracle, T, d, E, dtype, k, use_bias, normalize):
     assert np.abs(gp.cpu().numpy().astype(np.float64) - probs).max() <= 1e-6
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_gate_random_shapes(oracle, seed):
+    """Seeded sweep of the gate: token counts of every workgroup shape, feature counts that end
+    inside a stage, a tile or a step pair, 1 to 64 experts, k up to 4, both input types, strided x."""
+    rng = np.random.default_rng(4400 + seed)
+    E = int(rng.choice([1, 2, 5, 8, 12, 16, 17, 24, 32, 33, 48, 64]))
+    d = 8 * int(rng.integers(1, 140))
+    T = int(rng.choice([1, 15, 16, 17, 100, 1000, 4097, 9000, 20001, 40000, 70000]))
+    while T * d * E > 3e8:
+        T //= 2
+    k = int(rng.integers(1, min(E, 4) + 1))
+    dtype = "bf16" if rng.integers(0, 2) else "f32"
+    normalize = int(rng.integers(0, 2))
+    x = inputs.quantize(rng.standard_normal((T, d)), dtype)
+    Wg = (0.05 * rng.standard_normal((d, E))).astype(np.float32)
+    bias = (0.3 * rng.standard_normal(E)).astype(np.float32) if rng.integers(0, 2) else None
+    idx, w, probs = oracle.gate(x, Wg, bias, k, normalize)
+    pad = 8 * int(rng.integers(0, 3))                  # x as a view of wider rows
+    gfull = torch.zeros((T, d + pad), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device=DEV)
+    gfull[:, :d] = to_dev(x, dtype)
+    gx = gfull[:, :d]
+    gi, gw = _i32(T * k), torch.empty(T * k, dtype=torch.float32, device=DEV)
+    gp = torch.empty((T, E), dtype=torch.float32, device=DEV) if rng.integers(0, 2) else None
+    B.scmoe_gate_topk(gx, to_dev(Wg, "f32"), to_dev(bias, "f32"), k, gi, gw, gp, normalize=normalize)
+    torch.cuda.synchronize()
+    assert np.array_equal(gi.cpu().numpy().reshape(T, k), idx)
+    assert np.abs(gw.cpu().numpy().reshape(T, k).astype(np.float64) - w).max() <= 1e-6
+    if gp is not None:
+        assert np.abs(gp.cpu().numpy().astype(np.float64) - probs).max() <= 1e-6
+
+
 def test_gate_integer_ties_and_strided_view(oracle):
     """Integer inputs: logits exact, many ties, lowest index must win on both sides; x is
     passed as a strided view (ldx > d)."""
