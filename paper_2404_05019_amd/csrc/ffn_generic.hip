@@ -9,7 +9,8 @@
 namespace scmoe {
 
 constexpr int GT = 64;   // tile edge (rows and columns)
-constexpr int GK = 16;   // depth of one LDS stage
+constexpr int GK = 64;   // depth of one LDS stage (a stage is one round trip to memory: few, deep stages)
+constexpr int GQ = GT * GK / 256;   // elements of each operand a thread moves per stage
 
 template <bool BF16>
 __device__ __forceinline__ float load_elem(const unsigned char* p, int64_t i) {
@@ -28,8 +29,8 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(
     const unsigned char* __restrict__ A, int64_t lda, const int32_t* __restrict__ offsets, int E,
     int N, int Kd, const unsigned char* __restrict__ W, int64_t ldw, const float* __restrict__ bias,
     unsigned char* __restrict__ C, int64_t ldc, int gelu_mode) {
-  __shared__ float As[GK][GT + 1];
-  __shared__ float Bs[GK][GT + 1];
+  __shared__ __attribute__((aligned(16))) float As[GK][GT + 4];   // (rows stay 16-byte aligned: 4 values per read)
+  __shared__ __attribute__((aligned(16))) float Bs[GK][GT + 4];
   // which expert segment does this row tile belong to?
   int mt = blockIdx.x, e = 0, row0 = 0, row_end = 0;
   bool found = false;
@@ -55,23 +56,38 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
 
+  // The next stage's elements are fetched into registers while the current one is consumed
+  // (a tile of a small problem is a chain of Kd / GK round trips to memory otherwise).  Loads
+  // are unconditional on clamped indices; what lies outside the operands becomes zero.
+  float pa[GQ], pb[GQ];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int q = 0; q < GQ; ++q) {
+      const int idx = tid + q * 256;
+      const int r = idx / GK, kk = idx % GK;
+      const int row = row0 + r, kg = k0 + kk, n = n0 + r;
+      const int rowc = row < row_end ? row : row_end - 1, nc = n < N ? n : N - 1, kc = kg < Kd ? kg : Kd - 1;
+      const float av = load_elem<BF16>(A, static_cast<int64_t>(rowc) * lda + kc);
+      const float bv = load_elem<BF16>(We, static_cast<int64_t>(nc) * ldw + kc);
+      pa[q] = (row < row_end && kg < Kd) ? av : 0.0f;
+      pb[q] = (n < N && kg < Kd) ? bv : 0.0f;
+    }
+  };
+  fetch(0);
   for (int k0 = 0; k0 < Kd; k0 += GK) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < GQ; ++q) {
       const int idx = tid + q * 256;
-      const int r = idx >> 4, kk = idx & 15;
-      const int row = row0 + r, kg = k0 + kk, n = n0 + r;
-      As[kk][r] = (row < row_end && kg < Kd) ? load_elem<BF16>(A, static_cast<int64_t>(row) * lda + kg) : 0.0f;
-      Bs[kk][r] = (n < N && kg < Kd) ? load_elem<BF16>(We, static_cast<int64_t>(n) * ldw + kg) : 0.0f;
+      As[idx % GK][idx / GK] = pa[q];
+      Bs[idx % GK][idx / GK] = pb[q];
     }
     __syncthreads();
+    if (k0 + GK < Kd) fetch(k0 + GK);
 #pragma unroll
     for (int kk = 0; kk < GK; ++kk) {
-      float a[4], b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+      const float4 a4 = *reinterpret_cast<const float4*>(&As[kk][ty * 4]);
+      const float4 b4 = *reinterpret_cast<const float4*>(&Bs[kk][tx * 4]);
+      const float a[4] = {a4.x, a4.y, a4.z, a4.w}, b[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
