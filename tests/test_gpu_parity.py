@@ -41,7 +41,9 @@ def _i32(n, fill=None):
     # 17 to 64 experts: two or four accumulators per wave, tiles of 128 or 64 features
     (3000, 640, 32, "bf16", 1, True), (40000, 264, 24, "f32", 2, False), (9000, 520, 64, "bf16", 1, False),
     (2000, 1032, 48, "f32", 1, True), (70000, 128, 17, "bf16", 2, False), (20000, 392, 64, "f32", 3, True),
-    (5000, 2048, 64, "bf16", 1, False), (12000, 136, 33, "bf16", 4, True)])
+    (5000, 2048, 64, "bf16", 1, False), (12000, 136, 33, "bf16", 4, True),
+    # a few tokens with many experts: the one-lane-per-chain kernel
+    (100, 72, 40, "f32", 2, True), (60, 520, 64, "bf16", 1, False), (250, 136, 24, "bf16", 3, True)])
 @pytest.mark.parametrize("normalize", [0, 1])
 def test_gate_parity(oracle, T, d, E, dtype, k, use_bias, normalize):
     rng = np.random.default_rng(T + d + E)
